@@ -1,0 +1,162 @@
+/*
+ * mes.h -- C ABI of the MI355X (gfx950) mixed-precision delta linear layer.
+ *
+ * The operation is the serving hot path of ME-Switch (arXiv 2406.09041): every
+ * expert's weight is the shared pre-trained W_base plus a delta (Section 3,
+ * "delta = W_FT - W").  The delta's non-salient input channels are quantised to
+ * b = 1..3 bits with one step size per output channel (Eq. 1, Section 4.1), its k
+ * salient input channels stay in fp16 (Section 4.1, "Salient-aware delta
+ * selection", Eq. 2), and inference is decoupled as y = x W + x Delta~ (Eq. 4),
+ * batched across experts.
+ *
+ * Orientation: nn.Linear style.  W[d_out, d_in], y = x W^T.  A "step per output
+ * channel" is one float per ROW of the delta, a "salient input channel" is one
+ * COLUMN.  (The paper writes W[m, n] with m input channels.)
+ *
+ * Conventions
+ *  - Every data pointer is a DEVICE pointer unless its comment says HOST.
+ *  - The library never allocates or frees device memory.  The hot call
+ *    (mes_delta_linear) never synchronises; the offline calls that must report a
+ *    device-side check (mes_pack_delta) synchronise `stream` once before returning.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - All calls return a mes_status; mes_last_error() gives a thread-local message
+ *    for the last non-OK status.  All argument checks run on the host before any
+ *    HIP call.
+ *  - Shapes: d_in % 8 == 0 and d_out % 4 == 0 (row starts of x / y stay 16-byte /
+ *    8-byte aligned).  Stored matrices are zero padded to d_out_pad = ceil64(d_out),
+ *    d_in_pad = ceil512(d_in), k_pad = ceil32(k).
+ *
+ * Storage layouts (tile-major, so that one 64-lane wavefront reads contiguous
+ * memory and holds a matrix-core operand without any shuffle).  A "lane slot" is
+ * lane = 16 g + r: r = row inside a 16-row tile, g = which run of 8 consecutive
+ * columns inside a 32-column block.
+ *  - base:    uint16 (bf16 bits) [d_out_pad/16][d_in_pad/32][64 lanes][8];
+ *             slot (jt, kb, lane, e) holds W[16 jt + r][32 kb + 8 g + e].
+ *  - salient: uint16 (fp16 bits) [d_out_pad/16][k_pad/32][64][8];
+ *             slot (jt, sb, lane, e) holds fp16(Delta[16 jt + r][S[32 sb + 8 g + e]]).
+ *  - codes:   uint32 [d_out_pad/16][d_in_pad/KSTEP][planes][64 lanes], KSTEP = 64
+ *             (b = 2) or 128 (b = 1, 3); the lane's words hold the codes of row
+ *             16 jt + r at columns KSTEP ks + 32 m + 8 g + 2 q + h
+ *             (m < KSTEP/32, q < 4, h < 2):
+ *               b = 2: one word; code at bits [16 h + 2 (4 m + q), +2).
+ *               b = 1: one word; code at bit   16 h + (4 m + q).
+ *               b = 3: three words.  Word 0: low two code bits for m in {0,1} at
+ *                      bits [16 h + 2 p, +2), p = 4 m + q.  Word 1: the same for
+ *                      m in {2,3}, p = 4 (m - 2) + q.  Word 2: the high code bit;
+ *                      for m < 2 at bit 16 h + (p <= 6 ? 2 p + 2 : 0), for m >= 2 at
+ *                      bit 16 h + 2 p + 1.
+ *             Codes of salient columns, padding columns and padding rows are 0.
+ *    The code u is unsigned; the weight it stands for is (u - z) * step[row] with
+ *    z = 2^(b-1) - 1/2 (MES_GRID_SYM) or 2^(b-1) (MES_GRID_EQ1, Eq. 1's levels).
+ */
+#ifndef MES_H
+#define MES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MES_OK = 0,
+  MES_ERR_NULL = 1,      /* a required pointer is NULL                               */
+  MES_ERR_SHAPE = 2,     /* non-positive / unsupported / mismatching dimensions      */
+  MES_ERR_BITS = 3,      /* bits not in {1,2,3}, or a grid/step policy it excludes   */
+  MES_ERR_SALIENT = 4,   /* k out of range, or salient_idx not ascending / in range  */
+  MES_ERR_SEGMENTS = 5,  /* seg_offsets not 0 = o[0] <= ... <= o[E] = T              */
+  MES_ERR_ALIGN = 6,     /* a pointer is not 16-byte aligned                         */
+  MES_ERR_WORKSPACE = 7, /* workspace missing or too small                           */
+  MES_ERR_DEVICE = 8     /* a HIP call failed (message carries the HIP error string) */
+} mes_status;
+
+/* Quantisation grid (Eq. 1 and its symmetric variant). */
+enum { MES_GRID_SYM = 0, MES_GRID_EQ1 = 1 };
+/* Where the per-output-channel step comes from.  GIVEN: the caller's (e.g. learned by the
+ * distillation of Eq. 3); MAXABS: Eq. 1's initialisation max|X| / D over the non-salient
+ * columns of the row, D = 2^(b-1) - 1/2 (SYM) or 2^(b-1) - 1 (EQ1); MEANABS: b = 1 only,
+ * step = 2 * mean|X| (XNOR-Net scale). */
+enum { MES_STEP_GIVEN = 0, MES_STEP_MAXABS = 1, MES_STEP_MEANABS = 2 };
+
+#define MES_MAX_EXPERTS 64
+#define MES_LAYOUT_VERSION 1
+
+/* One expert's compressed delta for one linear layer (all pointers DEVICE, caller-owned). */
+typedef struct {
+  int32_t d_in, d_out, k, bits, grid, layout_version;
+  const void* codes;          /* mes_codes_bytes(d_in, d_out, bits) bytes, 16-byte aligned      */
+  const float* step;          /* [d_out], 16-byte aligned                                       */
+  const void* salient;        /* mes_salient_bytes(d_out, k) bytes of fp16, 16-byte aligned     */
+  const int32_t* salient_idx; /* [k] strictly ascending, 0 <= idx < d_in (may be NULL if k = 0) */
+} mes_delta;
+
+/* ---- sizes (pure host arithmetic; 0 on invalid arguments) ------------------------------------ */
+size_t mes_base_bytes(int d_in, int d_out);              /* tiled bf16 base                     */
+size_t mes_codes_bytes(int d_in, int d_out, int bits);   /* packed low-bit codes of one expert  */
+size_t mes_salient_bytes(int d_out, int k);              /* tiled fp16 salient columns          */
+size_t mes_pack_workspace_bytes(void);
+size_t mes_select_workspace_bytes(int n, int d_in, int d_out);
+size_t mes_linear_workspace_bytes(int d_in, int d_out, int max_tokens);
+const char* mes_last_error(void);
+int mes_layout_version(void);
+
+/* Re-tile the shared base weight (Eq. 4's W) for the kernels.  Offline.
+ * w: bf16 [d_out, d_in] row-major.  w_tiled_out: mes_base_bytes() bytes, fully overwritten. */
+mes_status mes_pack_base(const void* w, int d_in, int d_out, void* w_tiled_out, void* stream);
+/* Inverse of mes_pack_base (test / debug). */
+mes_status mes_unpack_base(const void* w_tiled, int d_in, int d_out, void* w_out, void* stream);
+
+/* Salient input-channel selection (Section 4.1, Eq. 2).  Offline.
+ * score_i = sum_t sum_j (x_ti D_ji - x_ti Dhat_ji)^2 with Dhat the b-bit quantisation of the
+ * whole delta (no salient set, step policy `step_policy`, never GIVEN); the k channels with
+ * the largest score are returned ascending (ties: the lower index wins).  fp64 arithmetic.
+ * delta: fp32 [d_out, d_in]; x_calib: fp32 [n, d_in]; idx_out: int32 [k];
+ * score_out: double [d_in] or NULL; workspace >= mes_select_workspace_bytes(n, d_in, d_out). */
+mes_status mes_select_salient(const float* delta, const float* x_calib, int n, int d_in, int d_out,
+                              int bits, int grid, int step_policy, int k, int32_t* idx_out,
+                              double* score_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Compress one expert's delta (Eq. 1 per output channel; salient columns kept in fp16).  Offline.
+ * delta: fp32 [d_out, d_in].  salient_idx: int32 [k] ascending (NULL if k = 0); checked on the
+ * device, MES_ERR_SALIENT if not strictly ascending or out of range (outputs then undefined).
+ * step_in: [d_out] for MES_STEP_GIVEN (entries that are not > 0 become 0), else ignored.
+ * Outputs, fully overwritten: codes_out (mes_codes_bytes), step_out [d_out] fp32,
+ * salient_out (mes_salient_bytes).  A row whose step is 0 stores code 2^(b-1) everywhere.
+ * Quantisation arithmetic is fp64: t = delta / step; SYM: u = clamp(floor(t) + 2^(b-1));
+ * EQ1: u = clamp(rint(t), -2^(b-1), 2^(b-1) - 1) + 2^(b-1).
+ * workspace >= mes_pack_workspace_bytes().  Synchronises `stream` once before returning. */
+mes_status mes_pack_delta(const float* delta, int d_in, int d_out, const int32_t* salient_idx, int k,
+                          int bits, int grid, int step_policy, const float* step_in, void* codes_out,
+                          float* step_out, void* salient_out, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* Expand a compressed delta (test / debug).  delta_hat_out: fp32 [d_out, d_in] = Delta~ of Eq. 4
+ * ((u - z) * step rounded once to fp32; fp16 values at salient columns) or NULL.
+ * codes_out: uint8 [d_out, d_in] (0xFF at salient columns) or NULL. */
+mes_status mes_unpack_delta(const mes_delta* d, float* delta_hat_out, uint8_t* codes_out, void* stream);
+
+/* Zero a mes_delta_linear workspace.  Call once after allocating it (mes_delta_linear leaves it
+ * ready for the next call). */
+mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* The hot path (Eq. 4, batched across experts):
+ *   y[t] = x[t] W_base^T + step_e .* (x_ns[t] (U_e - z)^T) + x_s[t] D_e^T,   e = expert of row t.
+ * w_base_tiled: output of mes_pack_base for [d_out, d_in].
+ * experts: HOST array [n_experts] (1 <= n_experts <= MES_MAX_EXPERTS) of descriptors whose
+ *          pointers are DEVICE; all must share d_in, d_out, k, bits, grid.  Read during the call only.
+ * x: bf16 [T, d_in] row-major, rows sorted by expert.  seg_offsets: HOST int32 [n_experts + 1],
+ *    0 = o[0] <= o[1] <= ... <= o[E] = T; rows o[e]..o[e+1] use expert e; an expert with an
+ *    empty segment costs no memory traffic.
+ * y: bf16 [T, d_out] row-major, fully overwritten (round-to-nearest-even from fp32 accumulators).
+ * workspace: >= mes_linear_workspace_bytes(d_in, d_out, T), initialised by mes_workspace_init;
+ *    calls sharing a workspace must be stream-ordered.
+ * T = 0 returns MES_OK without touching anything.  Enqueues on `stream`, never synchronises. */
+mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, int n_experts,
+                            const void* x, int T, const int32_t* seg_offsets, void* y,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MES_H */

@@ -1,0 +1,10 @@
+"""MI355X-native mixed-precision delta linear layer (ME-Switch serving hot path).
+
+The package is a thin binding over libmes.so (hand-written HIP kernels for gfx950 behind a C ABI,
+declared in include/mes.h).  Importing it without the built library raises ImportError.
+"""
+from .binding import (  # noqa: F401
+    GRID_EQ1, GRID_SYM, STEP_GIVEN, STEP_MAXABS, STEP_MEANABS, DeltaLinear, MesError, PackedDelta,
+    base_bytes, codes_bytes, linear_workspace_bytes, make_workspace, mes_delta_linear, mes_pack_base,
+    mes_pack_delta, mes_select_salient, mes_unpack_base, mes_unpack_delta, salient_bytes,
+)

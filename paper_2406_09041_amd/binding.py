@@ -1,0 +1,217 @@
+"""Thin ctypes binding over libmes.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch is used for device
+memory (tensors own every buffer) and for the current HIP stream.  There is no CPU
+fallback: if libmes.so is missing the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmes.so")
+
+MES_OK = 0
+GRID_SYM, GRID_EQ1 = 0, 1
+STEP_GIVEN, STEP_MAXABS, STEP_MEANABS = 0, 1, 2
+MAX_EXPERTS = 64
+
+STATUS_NAMES = {0: "MES_OK", 1: "MES_ERR_NULL", 2: "MES_ERR_SHAPE", 3: "MES_ERR_BITS", 4: "MES_ERR_SALIENT",
+                5: "MES_ERR_SEGMENTS", 6: "MES_ERR_ALIGN", 7: "MES_ERR_WORKSPACE", 8: "MES_ERR_DEVICE"}
+
+EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_workspace_bytes",
+           "mes_select_workspace_bytes", "mes_linear_workspace_bytes", "mes_last_error", "mes_layout_version",
+           "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
+           "mes_workspace_init", "mes_delta_linear"]
+
+
+class MesError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class mes_delta(ctypes.Structure):
+    _fields_ = [("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("bits", ctypes.c_int32), ("grid", ctypes.c_int32), ("layout_version", ctypes.c_int32),
+                ("codes", ctypes.c_void_p), ("step", ctypes.c_void_p), ("salient", ctypes.c_void_p),
+                ("salient_idx", ctypes.c_void_p)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_sz, vp = ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
+    lib.mes_base_bytes.restype = c_sz
+    lib.mes_base_bytes.argtypes = [c_int, c_int]
+    lib.mes_codes_bytes.restype = c_sz
+    lib.mes_codes_bytes.argtypes = [c_int, c_int, c_int]
+    lib.mes_salient_bytes.restype = c_sz
+    lib.mes_salient_bytes.argtypes = [c_int, c_int]
+    lib.mes_pack_workspace_bytes.restype = c_sz
+    lib.mes_pack_workspace_bytes.argtypes = []
+    lib.mes_select_workspace_bytes.restype = c_sz
+    lib.mes_select_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.mes_linear_workspace_bytes.restype = c_sz
+    lib.mes_linear_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.mes_last_error.restype = ctypes.c_char_p
+    lib.mes_last_error.argtypes = []
+    lib.mes_layout_version.restype = c_int
+    lib.mes_layout_version.argtypes = []
+    lib.mes_pack_base.restype = c_int
+    lib.mes_pack_base.argtypes = [vp, c_int, c_int, vp, vp]
+    lib.mes_unpack_base.restype = c_int
+    lib.mes_unpack_base.argtypes = [vp, c_int, c_int, vp, vp]
+    lib.mes_select_salient.restype = c_int
+    lib.mes_select_salient.argtypes = [vp, vp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, vp, vp, vp, c_sz, vp]
+    lib.mes_pack_delta.restype = c_int
+    lib.mes_pack_delta.argtypes = [vp, c_int, c_int, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp]
+    lib.mes_unpack_delta.restype = c_int
+    lib.mes_unpack_delta.argtypes = [ctypes.POINTER(mes_delta), vp, vp, vp]
+    lib.mes_workspace_init.restype = c_int
+    lib.mes_workspace_init.argtypes = [vp, c_sz, vp]
+    lib.mes_delta_linear.restype = c_int
+    lib.mes_delta_linear.argtypes = [vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
+                                     ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int) -> None:
+    if status != MES_OK:
+        raise MesError(status, lib.mes_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(device) -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream(device).cuda_stream)
+
+
+def base_bytes(d_in, d_out): return lib.mes_base_bytes(d_in, d_out)
+def codes_bytes(d_in, d_out, bits): return lib.mes_codes_bytes(d_in, d_out, bits)
+def salient_bytes(d_out, k): return lib.mes_salient_bytes(d_out, k)
+def linear_workspace_bytes(d_in, d_out, max_tokens): return lib.mes_linear_workspace_bytes(d_in, d_out, max_tokens)
+
+
+def mes_pack_base(w: torch.Tensor) -> torch.Tensor:
+    """w: bf16 [d_out, d_in] on the GPU -> tiled base (uint8 tensor of mes_base_bytes)."""
+    assert w.dtype == torch.bfloat16 and w.is_cuda and w.is_contiguous()
+    d_out, d_in = w.shape
+    out = torch.empty(base_bytes(d_in, d_out), dtype=torch.uint8, device=w.device)
+    _check(lib.mes_pack_base(_ptr(w), d_in, d_out, _ptr(out), _stream(w.device)))
+    return out
+
+
+def mes_unpack_base(w_tiled: torch.Tensor, d_in: int, d_out: int) -> torch.Tensor:
+    out = torch.empty((d_out, d_in), dtype=torch.bfloat16, device=w_tiled.device)
+    _check(lib.mes_unpack_base(_ptr(w_tiled), d_in, d_out, _ptr(out), _stream(w_tiled.device)))
+    return out
+
+
+@dataclass
+class PackedDelta:
+    """Device buffers of one expert's compressed delta (see include/mes.h for the layouts)."""
+    d_in: int
+    d_out: int
+    k: int
+    bits: int
+    grid: int
+    codes: torch.Tensor                  # uint8 [mes_codes_bytes]
+    step: torch.Tensor                   # fp32 [d_out]
+    salient: Optional[torch.Tensor]      # uint8 [mes_salient_bytes] or None
+    salient_idx: Optional[torch.Tensor]  # int32 [k] or None
+
+    def descriptor(self) -> mes_delta:
+        return mes_delta(self.d_in, self.d_out, self.k, self.bits, self.grid, lib.mes_layout_version(),
+                         self.codes.data_ptr(), self.step.data_ptr(),
+                         self.salient.data_ptr() if self.salient is not None else None,
+                         self.salient_idx.data_ptr() if self.salient_idx is not None else None)
+
+
+def mes_pack_delta(delta: torch.Tensor, salient_idx: Optional[torch.Tensor], bits: int, grid: int = GRID_SYM,
+                   step_policy: int = STEP_MAXABS, step_in: Optional[torch.Tensor] = None) -> PackedDelta:
+    """delta: fp32 [d_out, d_in] on the GPU; salient_idx: int32 [k] ascending (any device) or None."""
+    assert delta.dtype == torch.float32 and delta.is_cuda and delta.is_contiguous()
+    dev = delta.device
+    d_out, d_in = delta.shape
+    k = 0 if salient_idx is None else int(salient_idx.numel())
+    sidx = None if k == 0 else salient_idx.to(device=dev, dtype=torch.int32).contiguous()
+    codes = torch.empty(max(codes_bytes(d_in, d_out, bits), 16), dtype=torch.uint8, device=dev)
+    step = torch.empty(d_out, dtype=torch.float32, device=dev)
+    sal = None if k == 0 else torch.empty(salient_bytes(d_out, k), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lib.mes_pack_workspace_bytes(), dtype=torch.uint8, device=dev)
+    if step_in is not None:
+        step_in = step_in.to(device=dev, dtype=torch.float32).contiguous()
+    _check(lib.mes_pack_delta(_ptr(delta), d_in, d_out, _ptr(sidx), k, bits, grid, step_policy, _ptr(step_in),
+                              _ptr(codes), _ptr(step), _ptr(sal), _ptr(ws), ws.numel(), _stream(dev)))
+    return PackedDelta(d_in, d_out, k, bits, grid, codes, step, sal, sidx)
+
+
+def mes_unpack_delta(p: PackedDelta, want_codes: bool = True, want_delta: bool = True):
+    dev = p.codes.device
+    dh = torch.empty((p.d_out, p.d_in), dtype=torch.float32, device=dev) if want_delta else None
+    cd = torch.empty((p.d_out, p.d_in), dtype=torch.uint8, device=dev) if want_codes else None
+    desc = p.descriptor()
+    _check(lib.mes_unpack_delta(ctypes.byref(desc), _ptr(dh), _ptr(cd), _stream(dev)))
+    return dh, cd
+
+
+def mes_select_salient(delta: torch.Tensor, x_calib: torch.Tensor, bits: int, grid: int, k: int,
+                       step_policy: int = STEP_MAXABS, want_scores: bool = False):
+    """Eq. 2 selection.  Returns idx int32 [k] ascending (and the fp64 scores [d_in] if asked)."""
+    assert delta.dtype == torch.float32 and x_calib.dtype == torch.float32 and delta.is_cuda and x_calib.is_cuda
+    dev = delta.device
+    d_out, d_in = delta.shape
+    n = x_calib.shape[0]
+    idx = torch.empty(max(k, 1), dtype=torch.int32, device=dev)
+    score = torch.empty(d_in, dtype=torch.float64, device=dev) if want_scores else None
+    ws = torch.empty(max(lib.mes_select_workspace_bytes(n, d_in, d_out), 16), dtype=torch.uint8, device=dev)
+    _check(lib.mes_select_salient(_ptr(delta.contiguous()), _ptr(x_calib.contiguous()), n, d_in, d_out, bits, grid,
+                                  step_policy, k, _ptr(idx), _ptr(score), _ptr(ws), ws.numel(), _stream(dev)))
+    idx = idx[:k]
+    return (idx, score) if want_scores else idx
+
+
+def make_workspace(d_in: int, d_out: int, max_tokens: int, device) -> torch.Tensor:
+    """Allocates and initialises a mes_delta_linear workspace."""
+    n = max(linear_workspace_bytes(d_in, d_out, max_tokens), 16)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    _check(lib.mes_workspace_init(_ptr(ws), n, _stream(device)))
+    return ws
+
+
+class DeltaLinear:
+    """Marshalled arguments of mes_delta_linear for one layer (descriptor array built once)."""
+
+    def __init__(self, w_base_tiled: torch.Tensor, experts: Sequence[PackedDelta], max_tokens: int = 64,
+                 workspace: Optional[torch.Tensor] = None):
+        self.w = w_base_tiled
+        self.experts = list(experts)
+        self.E = len(self.experts)
+        self.d_in, self.d_out = self.experts[0].d_in, self.experts[0].d_out
+        self.desc = (mes_delta * self.E)(*[e.descriptor() for e in self.experts])
+        self.ws = workspace if workspace is not None else make_workspace(self.d_in, self.d_out, max_tokens, w_base_tiled.device)
+
+    def __call__(self, x: torch.Tensor, seg_offsets: Sequence[int], y: Optional[torch.Tensor] = None) -> torch.Tensor:
+        T = x.shape[0]
+        if y is None:
+            y = torch.empty((T, self.d_out), dtype=torch.bfloat16, device=x.device)
+        seg = (ctypes.c_int32 * (self.E + 1))(*seg_offsets)
+        _check(lib.mes_delta_linear(_ptr(self.w), self.desc, self.E, _ptr(x), T, seg, _ptr(y), _ptr(self.ws),
+                                    self.ws.numel(), _stream(x.device)))
+        return y
+
+
+def mes_delta_linear(w_base_tiled, experts, x, seg_offsets, y=None, workspace=None):
+    return DeltaLinear(w_base_tiled, experts, x.shape[0], workspace)(x, seg_offsets, y)

@@ -1,0 +1,51 @@
+// Internal declarations shared by the translation units of libmes (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mes.h"
+
+namespace mes {
+
+constexpr int kRowPad = 64;    // stored rows are padded to a multiple of this
+constexpr int kColPad = 512;   // stored columns are padded to a multiple of this
+constexpr int kSalPad = 32;    // stored salient columns are padded to a multiple of this
+constexpr int kTokGroup = 64;  // tokens one decode launch covers
+
+inline int ceil_to(int n, int m) { return (n + m - 1) / m * m; }
+inline int kstep_of(int bits) { return bits == 2 ? 64 : 128; }
+inline int planes_of(int bits) { return bits == 3 ? 3 : 1; }
+
+// Error plumbing (thread-local message, see mes_last_error()).
+mes_status fail(mes_status st, const char* fmt, ...);
+mes_status check_hip(hipError_t e, const char* what);
+
+// ---- launchers implemented in mes_pack.hip ------------------------------------------------------
+hipError_t launch_pack_base(const uint16_t* w, int d_in, int d_out, uint16_t* out, hipStream_t s);
+hipError_t launch_unpack_base(const uint16_t* t, int d_in, int d_out, uint16_t* out, hipStream_t s);
+hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int32_t* sidx, int k, int bits,
+                             int grid, int policy, const float* step_in, uint32_t* codes, float* step_out,
+                             uint16_t* sal, int* flag, hipStream_t s);
+hipError_t launch_unpack_delta(const mes_delta& d, float* delta_hat, uint8_t* codes_out, hipStream_t s);
+hipError_t launch_select(const float* delta, const float* xc, int n, int d_in, int d_out, int bits, int grid,
+                         int policy, int k, int32_t* idx_out, double* score_out, void* ws, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// ---- launcher implemented in mes_linear.hip -----------------------------------------------------
+struct LinearCall {
+  const void* w_base;
+  const mes_delta* experts;
+  int n_experts;
+  const void* x;
+  int T;
+  const int32_t* seg;
+  void* y;
+  void* ws;
+  size_t ws_bytes;
+};
+size_t linear_workspace_bytes(int d_in, int d_out, int max_tokens);
+hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
+
+}  // namespace mes

@@ -1,0 +1,353 @@
+// Offline kernels: re-tiling of the base weight, compression of one expert's delta
+// (Eq. 1 per output channel, fp16 salient columns -- Section 4.1), its inverse for tests,
+// and the salient-channel selection of Eq. 2.  None of these is on the serving path;
+// they are written for clarity and exact (fp64) arithmetic, not for speed.
+#include "mes_internal.h"
+
+#include <hip/hip_fp16.h>
+
+namespace mes {
+namespace {
+
+__device__ __forceinline__ bool is_salient(const int32_t* sidx, int k, int col, int* pos) {
+  int lo = 0, hi = k;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    int v = sidx[mid];
+    if (v < col) lo = mid + 1; else hi = mid;
+  }
+  if (lo < k && sidx[lo] == col) { if (pos) *pos = lo; return true; }
+  return false;
+}
+
+__device__ __forceinline__ double zero_point(int bits, int grid) {
+  return grid == MES_GRID_SYM ? (double)(1 << (bits - 1)) - 0.5 : (double)(1 << (bits - 1));
+}
+
+// Eq. 1 with an unsigned code: SYM takes the cell index floor(t), EQ1 rounds half to even.
+__device__ __forceinline__ uint32_t quant_code(float w, float step, int bits, int grid) {
+  const int half = 1 << (bits - 1);
+  if (!(step > 0.0f)) return (uint32_t)half;
+  double t = (double)w / (double)step;
+  double u;
+  if (grid == MES_GRID_SYM) {
+    u = floor(t) + (double)half;
+    u = fmin(fmax(u, 0.0), (double)(2 * half - 1));
+  } else {
+    u = fmin(fmax(rint(t), (double)-half), (double)(half - 1)) + (double)half;
+  }
+  return (uint32_t)(int)u;
+}
+
+// ---- base weight tiling --------------------------------------------------------------------------
+
+__global__ void k_pack_base(const uint16_t* __restrict__ w, int d_in, int d_out, int n_kb, size_t n_slots,
+                            uint4* __restrict__ out) {
+  size_t slot = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (slot >= n_slots) return;
+  int lane = (int)(slot & 63);
+  size_t blk = slot >> 6;
+  int kb = (int)(blk % n_kb);
+  int jt = (int)(blk / n_kb);
+  int row = 16 * jt + (lane & 15);
+  int col = 32 * kb + 8 * (lane >> 4);
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (row < d_out && col < d_in) v = *reinterpret_cast<const uint4*>(w + (size_t)row * d_in + col);
+  out[slot] = v;
+}
+
+__global__ void k_unpack_base(const uint4* __restrict__ t, int d_in, int d_out, int n_kb, size_t n_slots,
+                              uint16_t* __restrict__ w) {
+  size_t slot = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (slot >= n_slots) return;
+  int lane = (int)(slot & 63);
+  size_t blk = slot >> 6;
+  int kb = (int)(blk % n_kb);
+  int jt = (int)(blk / n_kb);
+  int row = 16 * jt + (lane & 15);
+  int col = 32 * kb + 8 * (lane >> 4);
+  if (row < d_out && col < d_in) *reinterpret_cast<uint4*>(w + (size_t)row * d_in + col) = t[slot];
+}
+
+// ---- delta compression -----------------------------------------------------------------------------
+
+__global__ void k_check_salient(const int32_t* __restrict__ sidx, int k, int d_in, int* flag) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= k) return;
+  int v = sidx[i];
+  bool bad = v < 0 || v >= d_in || (i > 0 && sidx[i - 1] >= v);
+  if (bad) atomicOr(flag, 1);
+}
+
+// One block per output channel.  MAXABS: exact max over the non-salient columns, then one fp64
+// division.  MEANABS: ascending sequential fp64 sum (thread 0), so the order is defined.
+__global__ void k_row_step(const float* __restrict__ delta, int d_in, const int32_t* __restrict__ sidx, int k,
+                           int bits, int grid, int policy, const float* __restrict__ step_in,
+                           float* __restrict__ step_out) {
+  const int row = blockIdx.x;
+  const float* r = delta + (size_t)row * d_in;
+  if (policy == MES_STEP_GIVEN) {
+    if (threadIdx.x == 0) { float s = step_in[row]; step_out[row] = s > 0.0f ? s : 0.0f; }
+    return;
+  }
+  if (policy == MES_STEP_MEANABS) {
+    if (threadIdx.x == 0) {
+      double tot = 0.0; int cnt = 0;
+      for (int c = 0; c < d_in; ++c)
+        if (!is_salient(sidx, k, c, nullptr)) { tot += (double)fabsf(r[c]); ++cnt; }
+      step_out[row] = cnt ? (float)(2.0 * (tot / (double)cnt)) : 0.0f;
+    }
+    return;
+  }
+  __shared__ float red[256];
+  float m = 0.0f;
+  for (int c = threadIdx.x; c < d_in; c += blockDim.x)
+    if (!is_salient(sidx, k, c, nullptr)) m = fmaxf(m, fabsf(r[c]));
+  red[threadIdx.x] = m;
+  __syncthreads();
+  for (int s = blockDim.x / 2; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    double div = grid == MES_GRID_SYM ? (double)(1 << (bits - 1)) - 0.5 : (double)(1 << (bits - 1)) - 1.0;
+    step_out[row] = (float)((double)red[0] / div);
+  }
+}
+
+// Bit position of the high code bit in word 2 of the 3-bit layout.
+__device__ __forceinline__ int hi_pos3(int m, int q) {
+  int p = 4 * (m & 1) + q;
+  return m < 2 ? (p <= 6 ? 2 * p + 2 : 0) : 2 * p + 1;
+}
+
+// One thread per stored code word.
+__global__ void k_pack_codes(const float* __restrict__ delta, int d_in, int d_out, const int32_t* __restrict__ sidx,
+                             int k, int bits, int grid, const float* __restrict__ step, int n_ks, size_t n_words,
+                             uint32_t* __restrict__ out) {
+  size_t widx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (widx >= n_words) return;
+  const int planes = bits == 3 ? 3 : 1;
+  const int n_m = bits == 2 ? 2 : 4;
+  const int kstep = 32 * n_m;
+  int lane = (int)(widx & 63);
+  size_t rest = widx >> 6;
+  int plane = (int)(rest % planes); rest /= planes;
+  int ks = (int)(rest % n_ks);
+  int jt = (int)(rest / n_ks);
+  int row = 16 * jt + (lane & 15);
+  int g = lane >> 4;
+  uint32_t word = 0;
+  if (row < d_out) {
+    const float s = step[row];
+    const float* r = delta + (size_t)row * d_in;
+    for (int m = 0; m < n_m; ++m) {
+      if (bits == 3 && plane == 0 && m >= 2) continue;
+      if (bits == 3 && plane == 1 && m < 2) continue;
+      for (int q = 0; q < 4; ++q)
+        for (int h = 0; h < 2; ++h) {
+          int col = kstep * ks + 32 * m + 8 * g + 2 * q + h;
+          if (col >= d_in || is_salient(sidx, k, col, nullptr)) continue;
+          uint32_t u = quant_code(r[col], s, bits, grid);
+          if (bits == 2) word |= u << (16 * h + 2 * (4 * m + q));
+          else if (bits == 1) word |= u << (16 * h + (4 * m + q));
+          else if (plane < 2) word |= (u & 3u) << (16 * h + 2 * (4 * (m & 1) + q));
+          else word |= (u >> 2) << (16 * h + hi_pos3(m, q));
+        }
+    }
+  }
+  out[widx] = word;
+}
+
+// `flag` was written by k_check_salient earlier on the same stream: with indices that failed the check
+// nothing is gathered (an index is never used as an address unless the whole list is valid).
+__global__ void k_pack_salient(const float* __restrict__ delta, int d_in, int d_out, const int32_t* __restrict__ sidx,
+                               int k, int n_sb, size_t n_elems, const int* __restrict__ flag,
+                               uint16_t* __restrict__ out) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_elems) return;
+  if (*flag) { out[idx] = 0; return; }
+  int e = (int)(idx & 7);
+  int lane = (int)((idx >> 3) & 63);
+  size_t blk = idx >> 9;
+  int sb = (int)(blk % n_sb);
+  int jt = (int)(blk / n_sb);
+  int row = 16 * jt + (lane & 15);
+  int rc = 32 * sb + 8 * (lane >> 4) + e;
+  uint16_t v = 0;
+  if (row < d_out && rc < k) {
+    const int col = min(max(sidx[rc], 0), d_in - 1);
+    __half h = __float2half_rn(delta[(size_t)row * d_in + col]);
+    v = __half_as_ushort(h);
+  }
+  out[idx] = v;
+}
+
+__device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, int n_ks, int row, int col) {
+  const int n_m = bits == 2 ? 2 : 4;
+  const int kstep = 32 * n_m;
+  const int planes = bits == 3 ? 3 : 1;
+  int jt = row >> 4, r = row & 15;
+  int ks = col / kstep, c = col % kstep;
+  int m = c >> 5, g = (c >> 3) & 3, q = (c >> 1) & 3, h = c & 1;
+  const uint32_t* w = codes + ((size_t)(jt * n_ks + ks) * planes) * 64 + (16 * g + r);
+  if (bits == 2) return (w[0] >> (16 * h + 2 * (4 * m + q))) & 3u;
+  if (bits == 1) return (w[0] >> (16 * h + (4 * m + q))) & 1u;
+  uint32_t lo = (w[(m < 2 ? 0 : 1) * 64] >> (16 * h + 2 * (4 * (m & 1) + q))) & 3u;
+  uint32_t hi = (w[2 * 64] >> (16 * h + hi_pos3(m, q))) & 1u;
+  return lo | (hi << 2);
+}
+
+__global__ void k_unpack_delta(const uint32_t* __restrict__ codes, const float* __restrict__ step,
+                               const uint16_t* __restrict__ sal, const int32_t* __restrict__ sidx, int d_in,
+                               int d_out, int k, int bits, int grid, int n_ks, int n_sb,
+                               float* __restrict__ delta_hat, uint8_t* __restrict__ codes_out) {
+  size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (size_t)d_in * d_out) return;
+  int row = (int)(idx / d_in), col = (int)(idx % d_in);
+  int pos = 0;
+  if (is_salient(sidx, k, col, &pos)) {
+    int jt = row >> 4, r = row & 15, sb = pos >> 5, g = (pos >> 3) & 3, e = pos & 7;
+    uint16_t hb = sal[(((size_t)(jt * n_sb + sb) * 64) + 16 * g + r) * 8 + e];
+    if (delta_hat) delta_hat[idx] = __half2float(__ushort_as_half(hb));
+    if (codes_out) codes_out[idx] = 0xFF;
+    return;
+  }
+  uint32_t u = load_code(codes, bits, n_ks, row, col);
+  if (codes_out) codes_out[idx] = (uint8_t)u;
+  if (delta_hat) delta_hat[idx] = (float)(((double)u - zero_point(bits, grid)) * (double)step[row]);
+}
+
+// ---- salient selection (Eq. 2) ------------------------------------------------------------------------
+// score_i = (sum_t x_ti^2) * (sum_j (D_ji - Dhat_ji)^2): the same number as the double sum of Eq. 2,
+// since x_ti factors out of each squared term.  One thread per input channel, ascending fp64 sums.
+__global__ void k_scores(const float* __restrict__ delta, const float* __restrict__ xc, int n, int d_in, int d_out,
+                         int bits, int grid, const float* __restrict__ step, double* __restrict__ score) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d_in) return;
+  const double z = zero_point(bits, grid);
+  double err = 0.0;
+  for (int j = 0; j < d_out; ++j) {
+    float w = delta[(size_t)j * d_in + i];
+    float s = step[j];
+    double wh = ((double)quant_code(w, s, bits, grid) - z) * (double)s;
+    double d = (double)w - wh;
+    err += d * d;
+  }
+  double xs = 0.0;
+  for (int t = 0; t < n; ++t) { double v = (double)xc[(size_t)t * d_in + i]; xs += v * v; }
+  score[i] = xs * err;
+}
+
+__global__ void k_rank(const double* __restrict__ score, int d_in, int k, int* __restrict__ chosen) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d_in) return;
+  double s = score[i];
+  int rank = 0;
+  for (int o = 0; o < d_in; ++o) {
+    double so = score[o];
+    rank += (so > s) || (so == s && o < i);
+  }
+  chosen[i] = rank < k;
+}
+
+__global__ void k_compact(const int* __restrict__ chosen, int d_in, int k, int32_t* __restrict__ idx_out) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d_in || !chosen[i]) return;
+  int pos = 0;
+  for (int o = 0; o < i; ++o) pos += chosen[o];
+  if (pos < k) idx_out[pos] = i;   // more than k can only be chosen when scores are NaN
+}
+
+__global__ void k_fill_zero(uint32_t* p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+inline unsigned blocks_for(size_t n, int bs) { return (unsigned)((n + bs - 1) / bs); }
+
+}  // namespace
+
+hipError_t launch_pack_base(const uint16_t* w, int d_in, int d_out, uint16_t* out, hipStream_t s) {
+  int n_kb = ceil_to(d_in, kColPad) / 32;
+  size_t n_slots = (size_t)(ceil_to(d_out, kRowPad) / 16) * n_kb * 64;
+  k_pack_base<<<blocks_for(n_slots, 256), 256, 0, s>>>(w, d_in, d_out, n_kb, n_slots, reinterpret_cast<uint4*>(out));
+  return hipGetLastError();
+}
+
+hipError_t launch_unpack_base(const uint16_t* t, int d_in, int d_out, uint16_t* out, hipStream_t s) {
+  int n_kb = ceil_to(d_in, kColPad) / 32;
+  size_t n_slots = (size_t)(ceil_to(d_out, kRowPad) / 16) * n_kb * 64;
+  k_unpack_base<<<blocks_for(n_slots, 256), 256, 0, s>>>(reinterpret_cast<const uint4*>(t), d_in, d_out, n_kb, n_slots, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  size_t n = bytes / 4;
+  if (n == 0) return hipSuccess;
+  k_fill_zero<<<blocks_for(n, 256), 256, 0, s>>>(reinterpret_cast<uint32_t*>(p), n);
+  return hipGetLastError();
+}
+
+hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int32_t* sidx, int k, int bits,
+                             int grid, int policy, const float* step_in, uint32_t* codes, float* step_out,
+                             uint16_t* sal, int* flag, hipStream_t s) {
+  hipError_t e;
+  k_fill_zero<<<1, 64, 0, s>>>(reinterpret_cast<uint32_t*>(flag), 1);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (k > 0) {
+    k_check_salient<<<blocks_for(k, 256), 256, 0, s>>>(sidx, k, d_in, flag);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  k_row_step<<<d_out, 256, 0, s>>>(delta, d_in, sidx, k, bits, grid, policy, step_in, step_out);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
+  int n_ks = pi / kstep_of(bits);
+  size_t n_words = (size_t)(po / 16) * n_ks * planes_of(bits) * 64;
+  k_pack_codes<<<blocks_for(n_words, 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, bits, grid, step_out, n_ks, n_words, codes);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (k > 0) {
+    int n_sb = ceil_to(k, kSalPad) / 32;
+    size_t n_el = (size_t)(po / 16) * n_sb * 512;
+    k_pack_salient<<<blocks_for(n_el, 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, n_sb, n_el, flag, sal);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_unpack_delta(const mes_delta& d, float* delta_hat, uint8_t* codes_out, hipStream_t s) {
+  int pi = ceil_to(d.d_in, kColPad);
+  int n_ks = pi / kstep_of(d.bits);
+  int n_sb = ceil_to(d.k, kSalPad) / 32;
+  size_t n = (size_t)d.d_in * d.d_out;
+  k_unpack_delta<<<blocks_for(n, 256), 256, 0, s>>>(reinterpret_cast<const uint32_t*>(d.codes), d.step,
+                                                    reinterpret_cast<const uint16_t*>(d.salient), d.salient_idx, d.d_in,
+                                                    d.d_out, d.k, d.bits, d.grid, n_ks, n_sb, delta_hat, codes_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const float* delta, const float* xc, int n, int d_in, int d_out, int bits, int grid,
+                         int policy, int k, int32_t* idx_out, double* score_out, void* ws, hipStream_t s) {
+  // workspace: double score[d_in] | float step[d_out] | int chosen[d_in]
+  char* p = reinterpret_cast<char*>(ws);
+  double* score = reinterpret_cast<double*>(p);
+  p += (size_t)ceil_to(d_in, 32) * sizeof(double);
+  float* step = reinterpret_cast<float*>(p);
+  p += (size_t)ceil_to(d_out, 64) * sizeof(float);
+  int* chosen = reinterpret_cast<int*>(p);
+  hipError_t e;
+  k_row_step<<<d_out, 256, 0, s>>>(delta, d_in, nullptr, 0, bits, grid, policy, nullptr, step);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  k_scores<<<blocks_for(d_in, 64), 64, 0, s>>>(delta, xc, n, d_in, d_out, bits, grid, step, score);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  k_rank<<<blocks_for(d_in, 256), 256, 0, s>>>(score, d_in, k, chosen);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (k > 0) {
+    k_compact<<<blocks_for(d_in, 256), 256, 0, s>>>(chosen, d_in, k, idx_out);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  if (score_out) e = hipMemcpyAsync(score_out, score, (size_t)d_in * sizeof(double), hipMemcpyDeviceToDevice, s);
+  return e;
+}
+
+}  // namespace mes

@@ -1,0 +1,136 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/mes.h declares, its size
+functions agree with the layout specification, and every argument error is caught on the host
+(before any HIP call), so none of these needs a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2406_09041_amd.binding as B
+from oracle import mes_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+lib = B.lib
+FAKE = 0x10000          # a non-null, 16-byte aligned address that is never dereferenced on the host
+ODD = 0x10004           # misaligned
+
+
+def test_every_declared_symbol_is_exported():
+    text = open(os.path.join(ROOT, "include", "mes.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(mes_[a-z_]+)\s*\(", text))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.mes_layout_version() == 1
+
+
+def test_size_functions_match_the_layout_specification():
+    for d_in, d_out, k in [(256, 256, 8), (4096, 4096, 64), (14336, 4096, 128), (4096, 14336, 64), (264, 72, 5), (8, 4, 0)]:
+        po, pi, pk = O.padded_dims(d_out, d_in, k)
+        assert lib.mes_base_bytes(d_in, d_out) == po * pi * 2
+        for bits in (1, 2, 3):
+            assert lib.mes_codes_bytes(d_in, d_out, bits) == O.codes_bytes(d_in, d_out, bits)
+        assert lib.mes_salient_bytes(d_out, k) == po * pk * 2
+        assert lib.mes_linear_workspace_bytes(d_in, d_out, 64) >= po // 16 * 4
+    assert lib.mes_codes_bytes(4096, 4096, 4) == 0
+    assert lib.mes_base_bytes(0, 4) == 0
+
+
+def _status(call):
+    st = call()
+    return st, lib.mes_last_error().decode()
+
+
+def test_pack_base_argument_errors():
+    st, msg = _status(lambda: lib.mes_pack_base(None, 64, 64, FAKE, None))
+    assert st == 1 and "null" in msg
+    assert lib.mes_pack_base(FAKE, 0, 64, FAKE, None) == 2
+    assert lib.mes_pack_base(FAKE, 60, 64, FAKE, None) == 2        # d_in % 8
+    assert lib.mes_pack_base(FAKE, 64, 62, FAKE, None) == 2        # d_out % 4
+    assert lib.mes_pack_base(ODD, 64, 64, FAKE, None) == 6
+
+
+def test_pack_delta_argument_errors():
+    def call(delta=FAKE, d_in=64, d_out=64, sidx=FAKE, k=4, bits=2, grid=0, pol=1, step_in=None, codes=FAKE,
+             step=FAKE, sal=FAKE, ws=FAKE, wsb=256):
+        return lib.mes_pack_delta(delta, d_in, d_out, sidx, k, bits, grid, pol, step_in, codes, step, sal, ws, wsb, None)
+    assert call(delta=None) == 1
+    assert call(bits=0) == 3 and call(bits=4) == 3
+    assert call(bits=1, grid=1) == 3                               # Eq. 1 grid has no 1-bit form
+    assert call(grid=2) == 3
+    assert call(pol=2, bits=2) == 3                                # MEANABS is the binary scale
+    assert call(pol=0, step_in=None) == 1                          # GIVEN needs step_in
+    assert call(k=-1) == 4 and call(k=65) == 4
+    assert call(sidx=None) == 1 and call(sal=None) == 1
+    assert call(codes=ODD) == 6
+    assert call(ws=None) == 7 and call(wsb=8) == 7
+    assert call(d_in=-8) == 2
+
+
+def test_select_argument_errors():
+    def call(delta=FAKE, xc=FAKE, n=4, d_in=64, d_out=64, bits=2, grid=0, pol=1, k=4, idx=FAKE, score=None, ws=FAKE, wsb=1 << 20):
+        return lib.mes_select_salient(delta, xc, n, d_in, d_out, bits, grid, pol, k, idx, score, ws, wsb, None)
+    assert call(xc=None) == 1
+    assert call(n=0) == 2
+    assert call(pol=0) == 3                                        # selection never takes a given step
+    assert call(k=65) == 4
+    assert call(idx=None) == 1
+    assert call(wsb=16) == 7
+
+
+def _desc(**kw):
+    d = dict(d_in=64, d_out=64, k=4, bits=2, grid=0, layout_version=1, codes=FAKE, step=FAKE, salient=FAKE, salient_idx=FAKE)
+    d.update(kw)
+    return B.mes_delta(**d)
+
+
+def _linear(descs, T, seg, w=FAKE, x=FAKE, y=FAKE, ws=FAKE, wsb=1 << 30):
+    arr = (B.mes_delta * len(descs))(*descs)
+    segc = (ctypes.c_int32 * len(seg))(*seg)
+    return lib.mes_delta_linear(w, arr, len(descs), x, T, segc, y, ws, wsb, None)
+
+
+def test_delta_linear_argument_errors():
+    d = _desc()
+    assert _linear([d], 4, [0, 4], w=None) == 1
+    assert _linear([d], 4, [1, 4]) == 5                            # must start at 0
+    assert _linear([d, d], 4, [0, 3, 2]) == 5                      # decreasing
+    assert _linear([d, d], 4, [0, 2, 3]) == 5                      # must end at T
+    assert _linear([d], -1, [0, -1]) == 2
+    assert _linear([d, _desc(k=8)], 4, [0, 2, 4]) == 2             # experts must agree
+    assert _linear([d, _desc(bits=3)], 4, [0, 2, 4]) == 2
+    assert _linear([_desc(bits=5)], 4, [0, 4]) == 3
+    assert _linear([_desc(layout_version=7)], 4, [0, 4]) == 2
+    assert _linear([_desc(codes=None)], 4, [0, 4]) == 1
+    assert _linear([_desc(salient_idx=None)], 4, [0, 4]) == 1
+    assert _linear([_desc(step=ODD)], 4, [0, 4]) == 6
+    assert _linear([d], 4, [0, 4], x=ODD) == 6
+    assert _linear([d], 4, [0, 4], ws=None) == 7
+    assert _linear([d], 4, [0, 4], wsb=4) == 7
+    assert "workspace needs" in lib.mes_last_error().decode()
+    # T = 0 is a no-op that never touches a pointer
+    assert _linear([d], 0, [0, 0], w=None, x=None, y=None, ws=None, wsb=0) == 0
+    arr = (B.mes_delta * 1)(d)
+    assert lib.mes_delta_linear(FAKE, arr, 65, FAKE, 4, (ctypes.c_int32 * 2)(0, 4), FAKE, FAKE, 1 << 30, None) == 2
+
+
+def test_unpack_and_workspace_init_argument_errors():
+    d = _desc()
+    assert lib.mes_unpack_delta(ctypes.byref(d), None, None, None) == 1
+    assert lib.mes_unpack_delta(None, FAKE, None, None) == 1
+    assert lib.mes_workspace_init(None, 64, None) == 1
+    assert lib.mes_workspace_init(ODD, 64, None) == 6
+
+
+def test_no_cpu_fallback_in_the_product_path():
+    """The binding and the library sources never import or include the oracle."""
+    pkg = os.path.join(ROOT, "paper_2406_09041_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src, os.path.join(dirpath, f)
