@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision delta linear hot path on one MI355X.
+
+Workload (config "c4", the one the headline metric is quoted on): the seven linear shapes of one
+Mistral-7B block, 16 experts resident, a decode batch of 64 tokens routed Zipf(1.1), 2-bit
+non-salient codes, 64 fp16 salient input channels.  One "step" = one pass of that batch through
+all seven linears (seven mes_delta_linear calls).  A token = one row of x through all seven.
+
+Prints ONE JSON line.  `value` is tokens/s with every input already resident in HBM.
+`roofline` prices the hot kernel against the HBM peak with ALGORITHMIC bytes; `cpu_baseline`
+times the fp64 oracle on a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def algorithmic_bytes(d_in, d_out, k, bits, n_active, T):
+    """Bytes the method must move for one call: base once, each ACTIVE expert's compact codes, fp16
+    salient columns, steps and indices, plus x in and y out.  Padding, codes stored at salient
+    columns and workspace traffic are not credited."""
+    base = 2 * d_out * d_in
+    per_expert = d_out * (d_in - k) * bits // 8 + 2 * d_out * k + 4 * d_out + 4 * k
+    return base + n_active * per_expert + 2 * T * d_in + 2 * T * d_out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c4", choices=["c4", "c2"])
+    ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every linear on its own (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU; --gpus must be 1 (nothing here uses a second GPU).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2406_09041_amd as mes
+    from inputs import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # ---------------------------------------------------------------- build the workload in HBM
+    layers = []          # one entry per mes_delta_linear call of a step
+    samples = []         # what the oracle leg needs (a seeded sample of output channels), kept on the host
+    g = torch.Generator().manual_seed(4242)
+    if args.workload == "c4":
+        names = [n for n, _, _ in synth.MISTRAL7B_LINEARS]
+        wls = [(n, lambda n=n: synth.config4_linear(n, device=dev, bits=args.bits)) for n in names]
+        sample_frac = 8
+        copies = 1
+    else:
+        # 48 MB per call fits the 256 MB Infinity Cache: rotate over independent copies so every call streams from HBM
+        copies = 14
+        wls = [(f"q_proj#{c}", lambda c=c: synth.config2(device=dev, copy=c)) for c in range(copies)]
+        sample_frac = 8
+    T = None
+    for name, make in wls:
+        wl = make()
+        T = wl.x.shape[0]
+        w_t = mes.mes_pack_base(wl.w_base)
+        packed = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]
+        lin = mes.DeltaLinear(w_t, packed, T)
+        y = torch.empty((T, wl.d_out), dtype=torch.bfloat16, device=dev)
+        n_active = sum(1 for e in range(len(packed)) if wl.seg_offsets[e + 1] > wl.seg_offsets[e])
+        layers.append(dict(name=name, lin=lin, x=wl.x, seg=wl.seg_offsets, y=y, d_in=wl.d_in, d_out=wl.d_out,
+                           k=wl.k, bits=wl.bits, n_active=n_active,
+                           bytes=algorithmic_bytes(wl.d_in, wl.d_out, wl.k, wl.bits, n_active, T)))
+        if not args.no_cpu_baseline and (args.workload == "c4" or len(samples) == 0):
+            rows = torch.sort(torch.randperm(wl.d_out, generator=g)[: max(wl.d_out // sample_frac, 16)]).values
+            rd = rows.to(dev)
+            samples.append(dict(name=name, rows=rows, layer=len(layers) - 1,
+                                w=wl.w_base[rd].double().cpu().numpy(), x=wl.x.double().cpu().numpy(),
+                                deltas=[ex.delta[rd].cpu().numpy() for ex in wl.experts],
+                                sidx=[ex.salient_idx.numpy() for ex in wl.experts], seg=wl.seg_offsets,
+                                bits=wl.bits, d_out=wl.d_out))
+        del wl
+    torch.cuda.synchronize()
+    calls_per_step = 7 if args.workload == "c4" else 1
+
+    def one_step(i):
+        if args.workload == "c4":
+            for L in layers:
+                L["lin"](L["x"], L["seg"], L["y"])
+        else:
+            L = layers[i % copies]
+            L["lin"](L["x"], L["seg"], L["y"])
+
+    # ---------------------------------------------------------------- timed region
+    for i in range(args.warmup):
+        one_step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        one_step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall0
+    ms_total = ev0.elapsed_time(ev1)
+    ms_per_step = ms_total / args.steps
+    tokens_per_s = T * args.steps / (ms_total * 1e-3)
+
+    step_bytes = sum(L["bytes"] for L in layers) if args.workload == "c4" else layers[0]["bytes"]
+    launch_bytes = step_bytes / calls_per_step
+    launch_ms = ms_per_step / calls_per_step
+    achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{args.workload}_b{args.bits}", {}).get("bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    breakdown = None
+    if args.breakdown and args.workload == "c4":
+        breakdown = {}
+        for L in layers:
+            for _ in range(5):
+                L["lin"](L["x"], L["seg"], L["y"])
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            # interleave with a big other matrix so this one is not served from the Infinity Cache
+            other = layers[4] if L is not layers[4] else layers[5]
+            reps, tot = 20, 0.0
+            for _ in range(reps):
+                other["lin"](other["x"], other["seg"], other["y"])
+                a.record()
+                L["lin"](L["x"], L["seg"], L["y"])
+                b.record()
+                torch.cuda.synchronize()
+                tot += a.elapsed_time(b)
+            us = tot / reps * 1e3
+            breakdown[L["name"]] = dict(us=round(us, 2), GBs=round(L["bytes"] / us / 1e3, 1), MB=round(L["bytes"] / 1e6, 2))
+        print("breakdown:", json.dumps(breakdown), file=sys.stderr)
+
+    # ---------------------------------------------------------------- oracle leg (baseline only)
+    cpu_baseline = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import mes_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        prepared = []
+        for s in samples:           # offline compression of the sampled rows is not part of the timed oracle work
+            exs = []
+            for d, si in zip(s["deltas"], s["sidx"]):
+                c, st, sal = O.quantize(d, si, s["bits"])
+                exs.append(dict(codes=c, step=st, salient=sal, salient_idx=si, bits=s["bits"], grid=O.GRID_SYM))
+            prepared.append(exs)
+        t0 = time.perf_counter()
+        refs = [O.delta_linear(s["x"], s["w"], exs, s["seg"]) for s, exs in zip(samples, prepared)]
+        t_cpu = time.perf_counter() - t0
+        # scale the sampled rows to the full step: every linear was sampled at the same fraction of its rows
+        frac = sum(len(s["rows"]) * s["x"].shape[1] for s in samples) / sum(s["d_out"] * s["x"].shape[1] for s in samples)
+        cpu_tokens_per_s = T / (t_cpu / frac)
+        num = den = 0.0
+        for s, ref in zip(samples, refs):
+            yg = layers[s["layer"]]["y"][:, s["rows"].to(dev)].double().cpu().numpy()
+            num += float(((yg - ref) ** 2).sum())
+            den += float((ref ** 2).sum())
+        parity = (num / den) ** 0.5
+        cpu_baseline = dict(value=round(cpu_tokens_per_s, 2), unit="tokens/s", cores=int(cores), kind="oracle",
+                            sample=f"fp64 numpy oracle on a seeded 1/{sample_frac} sample of the output channels of "
+                                   f"{'each of the 7 linears' if args.workload == 'c4' else 'one q_proj copy'}, all {T} tokens "
+                                   f"and all experts ({t_cpu:.2f} s of CPU work), scaled linearly by rows (extrapolated)")
+
+    out = {
+        "metric": "tokens/s + achieved HBM GB/s, 16-expert Mistral-7B-shape decode delta linear",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": ("c4: 7 Mistral-7B linear shapes of one block, 16 experts, 64 decode tokens, Zipf(1.1) routing, "
+                                f"{args.bits}-bit codes, 64 fp16 salient channels") if args.workload == "c4" else
+                               "c2: Mistral-7B q_proj 4096x4096, 3 experts, 48 decode tokens 16/16/16, 2-bit, 64 salient; "
+                               f"{copies} rotating copies",
+                   "tokens": T, "experts": 16 if args.workload == "c4" else 3, "bits": args.bits,
+                   "calls_per_step": calls_per_step,
+                   "active_experts": layers[0]["n_active"]},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": "k_delta_linear", "algorithmic_bytes_per_launch": int(launch_bytes),
+                     "avg_launch_us": round(launch_ms * 1e3, 3)},
+        "cpu_baseline": cpu_baseline,
+        "parity_rel_fro_vs_oracle_sample": None if parity is None else float(f"{parity:.3e}"),
+        "host_wall_ms_per_step": round(t_wall / args.steps * 1e3, 5),
+    }
+    if breakdown:
+        out["breakdown"] = breakdown
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
