@@ -62,13 +62,21 @@ struct LinearParams {
   const u32x4* sal[kMaxSlots];
   const int32_t* sidx[kMaxSlots];
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
-  uint8_t vis_slot[kMaxVisits + 1], vis_tt[kMaxVisits + 1];
-  int d_in, d_out, d_out_pad, n_kb, n_chunks, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
+  uint8_t vis_slot[kMaxVisits + 1], vis_tt[kMaxVisits + 1];   // visits in tile-major order
+  uint32_t vis_mask[kMaxVisits + 1];      // bit n: token 16 tt + n of the visit's tile belongs to the visit's expert
+  int tile_beg[5];                        // visits tile_beg[tt] .. tile_beg[tt + 1] are the ones of tile tt
+  int d_in, d_out, d_out_pad, n_kb, n_chunks, n_sb, k, T, t0, n_act, n_vis, n_vis_all, nsplit, bits;
   float z;
 };
 
 __device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// acc += A x B with the accumulator updated in place.  Used where the update sits under a (wave-uniform)
+// branch: tying source and destination keeps the compiler from copying accumulators around the branch.
+__device__ __forceinline__ void mfma16_acc(f32x4& acc, u32x4 a, u32x4 b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
 }
 
 // (a & mask) | orv in one VALU operation (the mask rides the scalar operand slot).
@@ -246,101 +254,61 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
 
 // ---- main kernel ------------------------------------------------------------------------------------
 
-// Everything one wavefront streams for one step, held in registers: the loads of the wavefront's next
-// step are issued before the arithmetic of the current one.
-template <int BITS, int R, int TT, int NA>
-struct StepBuf {
-  u32x4 base[R][Codec<BITS>::NM];
+// Loads are written as (wave-uniform pointer) + (32-bit unsigned lane offset): the pointer then lives in
+// scalar registers and one vector register per lane serves every stream.
+__device__ __forceinline__ u32x4 ld128(const void* uniform_ptr, uint32_t lane_off) {
+  return *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(uniform_ptr) + lane_off);
+}
+__device__ __forceinline__ uint32_t ld32(const void* uniform_ptr, uint32_t lane_off) {
+  return *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(uniform_ptr) + lane_off);
+}
+
+// x where the lane's bit of `lane_mask` is set, else 0 (the mask rides a scalar register pair).
+__device__ __forceinline__ uint32_t keep_if(uint32_t x, uint64_t lane_mask) {
+  uint32_t d;
+  asm("v_cndmask_b32 %0, 0, %1, %2" : "=v"(d) : "v"(x), "s"(lane_mask));
+  return d;
+}
+
+template <int BITS, int TT>
+struct ActBuf {
   u32x4 xb[TT][Codec<BITS>::NM];
-  uint32_t cw[NA][R][Codec<BITS>::PLANES];
 };
 
-// Every load here is unconditional and in a fixed order, so that the compiler can wait for exactly the
-// loads a computation needs while younger ones stay in flight (slots past n_act alias slot 0's codes;
-// the host fills them in).
-template <int BITS, int R, int TT, int NA>
-__device__ __forceinline__ void load_step(const LinearParams& p, int s, int lane, int jt0, int n_steps,
-                                          StepBuf<BITS, R, TT, NA>& b) {
+template <int BITS, int TT>
+__device__ __forceinline__ void load_act(const LinearParams& p, int s, int lane, ActBuf<BITS, TT>& b) {
+  using C = Codec<BITS>;
+  const char* src = reinterpret_cast<const char*>(p.xt) + (size_t)s * (C::NM * 4 * 1024);
+#pragma unroll
+  for (int m = 0; m < C::NM; ++m)
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) b.xb[tt][m] = ld128(src + (m * 4 + tt) * 1024, (uint32_t)lane * 16u);
+}
+
+template <int BITS, int R>
+__device__ __forceinline__ void load_base(const LinearParams& p, int s, int lane, int jt0, u32x4 (&base)[R][Codec<BITS>::NM]) {
   using C = Codec<BITS>;
 #pragma unroll
-  for (int m = 0; m < C::NM; ++m)
+  for (int rt = 0; rt < R; ++rt) {
+    const char* src = reinterpret_cast<const char*>(p.w_base) + ((size_t)(jt0 + rt) * p.n_kb + (size_t)s * C::NM) * 1024;
 #pragma unroll
-    for (int rt = 0; rt < R; ++rt)
-      b.base[rt][m] = p.w_base[((size_t)(jt0 + rt) * p.n_kb + (s * C::NM + m)) * 64 + lane];
-#pragma unroll
-  for (int m = 0; m < C::NM; ++m)
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) b.xb[tt][m] = p.xt[((size_t)(s * C::NM + m) * 4 + tt) * 64 + lane];
-#pragma unroll
-  for (int a = 0; a < NA; ++a) {
-#pragma unroll
-    for (int rt = 0; rt < R; ++rt) {
-      const uint32_t* src = p.codes[a] + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 64) + lane;
-#pragma unroll
-      for (int pl = 0; pl < C::PLANES; ++pl) b.cw[a][rt][pl] = src[pl * 64];
-    }
+    for (int m = 0; m < C::NM; ++m) base[rt][m] = ld128(src + m * 1024, (uint32_t)lane * 16u);
   }
 }
 
-// One expert's low-bit product for one step: dequantise once per 16-row tile, then one MFMA per column
-// block and token tile the expert has tokens in.  A tile that is entirely the expert's needs no masking.
-template <int BITS, int R, int TT>
-__device__ __forceinline__ void expert_step(const uint32_t (&cw)[R][Codec<BITS>::PLANES], const u32x4 (&xb)[TT][Codec<BITS>::NM],
-                                            int lo, int hi, int n, f32x4 (&acc_raw)[R][TT]) {
+// Code words of step s for the first NA active slots (slots past n_act alias slot 0; the host fills them in).
+template <int BITS, int R, int NA>
+__device__ __forceinline__ void load_codes(const LinearParams& p, int s, int lane, int jt0, int n_steps,
+                                           uint32_t (&cw)[NA][R][Codec<BITS>::PLANES]) {
   using C = Codec<BITS>;
-  u32x4 dq[R][C::NM];
-#pragma unroll
-  for (int rt = 0; rt < R; ++rt) C::dequant(cw[rt], dq[rt]);
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) {
-    if (16 * tt < hi && 16 * tt + 16 > lo) {
-      if (lo <= 16 * tt && hi >= 16 * tt + 16) {
-#pragma unroll
-        for (int m = 0; m < C::NM; ++m)
-#pragma unroll
-          for (int rt = 0; rt < R; ++rt) acc_raw[rt][tt] = mfma16(dq[rt][m], xb[tt][m], acc_raw[rt][tt]);
-      } else {
-        const int tl = 16 * tt + n;
-        const bool inm = tl >= lo && tl < hi;
-#pragma unroll
-        for (int m = 0; m < C::NM; ++m) {
-          u32x4 xm;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) xm[q] = inm ? xb[tt][m][q] : 0u;
-#pragma unroll
-          for (int rt = 0; rt < R; ++rt) acc_raw[rt][tt] = mfma16(dq[rt][m], xm, acc_raw[rt][tt]);
-        }
-      }
-    }
-  }
-}
-
-template <int BITS, int R, int TT, int NA>
-__device__ __forceinline__ void compute_step(const LinearParams& p, int s, int lane, int jt0, int n_steps,
-                                             const StepBuf<BITS, R, TT, NA>& b, f32x4 (&acc_base)[R][TT],
-                                             f32x4 (&acc_raw)[R][TT]) {
-  using C = Codec<BITS>;
-  const int n = lane & 15;
-#pragma unroll
-  for (int m = 0; m < C::NM; ++m)
-#pragma unroll
-    for (int rt = 0; rt < R; ++rt)
-#pragma unroll
-      for (int tt = 0; tt < TT; ++tt) acc_base[rt][tt] = mfma16(b.base[rt][m], b.xb[tt][m], acc_base[rt][tt]);
 #pragma unroll
   for (int a = 0; a < NA; ++a)
-    if (a < p.n_act) expert_step<BITS, R, TT>(b.cw[a], b.xb, p.lo[a], p.hi[a], n, acc_raw);
-  // more active experts than prefetch slots (needs > 16 experts inside one 64-token group): load on demand
-  for (int a = NA; a < p.n_act; ++a) {
-    uint32_t cw[R][C::PLANES];
 #pragma unroll
     for (int rt = 0; rt < R; ++rt) {
-      const uint32_t* src = p.codes[a] + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 64) + lane;
+      const char* src = reinterpret_cast<const char*>(p.codes[a]) + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 256);
 #pragma unroll
-      for (int pl = 0; pl < C::PLANES; ++pl) cw[rt][pl] = src[pl * 64];
+      for (int pl = 0; pl < C::PLANES; ++pl) cw[a][rt][pl] = ld32(src + pl * 256, (uint32_t)lane * 4u);
     }
-    expert_step<BITS, R, TT>(cw, b.xb, p.lo[a], p.hi[a], n, acc_raw);
-  }
 }
 
 // One (visit, 32-salient-column block) pair of the fp16 product.
@@ -354,9 +322,10 @@ template <int R>
 __device__ __forceinline__ void load_sal(const LinearParams& p, int pair, int lane, int jt0, SalBuf<R>& b) {
   const int v = pair / p.n_sb, sb = pair - v * p.n_sb;
   const int a = p.vis_slot[v];
-  b.xs = p.xs[((size_t)v * p.n_sb + sb) * 64 + lane];
+  b.xs = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)v * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
 #pragma unroll
-  for (int rt = 0; rt < R; ++rt) b.d[rt] = p.sal[a][((size_t)(jt0 + rt) * p.n_sb + sb) * 64 + lane];
+  for (int rt = 0; rt < R; ++rt)
+    b.d[rt] = ld128(reinterpret_cast<const char*>(p.sal[a]) + ((size_t)(jt0 + rt) * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
 }
 
 template <int R, int TT>
@@ -376,10 +345,73 @@ __device__ __forceinline__ void compute_sal(const LinearParams& p, int pair, con
   }
 }
 
+// Per-wavefront LDS: the code words of the current step, [slot][row tile][plane][lane], so that the loop
+// over the experts of a token tile can index experts at run time (registers cannot be indexed that way).
+template <int BITS, int R, int NA>
+struct CodeStore {
+  uint32_t w[NA][R][Codec<BITS>::PLANES][64];
+};
+
+// Arithmetic of one step.  Token tiles are walked in a fixed (unrolled) order; the experts that have tokens
+// in a tile are walked by a plain loop over the host-built visit table, whose body has no branch: read the
+// expert's code words from LDS, dequantise, zero the lanes of other experts' tokens, accumulate.
+template <int BITS, int R, int TT, int NA>
+__device__ __forceinline__ void compute_step(const LinearParams& p, int s, int s_next, int lane, int jt0, int n_steps,
+                                             u32x4 (&base)[R][Codec<BITS>::NM], const ActBuf<BITS, TT>& x,
+                                             const CodeStore<BITS, R, NA>& cs, const uint32_t* vis_lds,
+                                             f32x4 (&acc_base)[R][TT], f32x4 (&acc_raw)[R][TT]) {
+  using C = Codec<BITS>;
+#pragma unroll
+  for (int m = 0; m < C::NM; ++m)
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) acc_base[rt][tt] = mfma16(base[rt][m], x.xb[tt][m], acc_base[rt][tt]);
+  load_base<BITS, R>(p, s_next, lane, jt0, base);   // reloaded in place for the next step, a full step ahead
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    const int v_end = p.tile_beg[tt + 1];
+    for (int v = p.tile_beg[tt]; v < v_end; ++v) {
+      // visit descriptor: slot and the 16-bit token mask of the tile, replicated over the four lane groups
+      const uint32_t slot = __builtin_amdgcn_readfirstlane(vis_lds[2 * v]);
+      const uint32_t m16 = __builtin_amdgcn_readfirstlane(vis_lds[2 * v + 1]);
+      const uint64_t lane_mask = ((uint64_t)m16 << 32) | m16;
+      u32x4 dq[R][C::NM];
+      if (slot < (uint32_t)NA) {
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+          uint32_t cw[C::PLANES];
+#pragma unroll
+          for (int pl = 0; pl < C::PLANES; ++pl) cw[pl] = cs.w[slot][rt][pl][lane];
+          C::dequant(cw, dq[rt]);
+        }
+      } else {   // more active experts than prefetch slots (> 16 experts inside one 64-token group): load on demand
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) {
+          uint32_t cw[C::PLANES];
+          const char* src = reinterpret_cast<const char*>(p.codes[slot]) + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 256);
+#pragma unroll
+          for (int pl = 0; pl < C::PLANES; ++pl) cw[pl] = ld32(src + pl * 256, (uint32_t)lane * 4u);
+          C::dequant(cw, dq[rt]);
+        }
+      }
+#pragma unroll
+      for (int m = 0; m < C::NM; ++m) {
+        u32x4 xm;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xm[q] = keep_if(x.xb[tt][m][q], lane_mask);
+#pragma unroll
+        for (int rt = 0; rt < R; ++rt) acc_raw[rt][tt] = mfma16(dq[rt][m], xm, acc_raw[rt][tt]);
+      }
+    }
+  }
+}
+
 template <int BITS, int R, int TT, int NA, int NW>
 __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) {
   using C = Codec<BITS>;
   constexpr int SPC = 128 / C::KSTEP;  // steps per 128-column chunk
+  constexpr bool XDB = C::NM * TT <= 8;   // double-buffer the activation operands when they fit in registers
   const int lane = threadIdx.x & 63;
   // The wavefront index is the same in all 64 lanes; saying so keeps every value derived from it (step
   // numbers, addresses, which token tile a salient pair belongs to) in scalar registers and every branch on
@@ -393,6 +425,17 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int s_begin = (int)((long)sp * p.n_chunks / p.nsplit) * SPC;
   const int s_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit) * SPC;
 
+  constexpr int kCodeBytes = (int)sizeof(CodeStore<BITS, R, NA>) * NW;
+  constexpr int kRedBytes = NW * R * TT * 4 * 64 * 4;
+  __shared__ __attribute__((aligned(16))) char smem[kCodeBytes > kRedBytes ? kCodeBytes : kRedBytes];
+  __shared__ uint32_t vis_lds[2 * (kMaxVisits + 1)];
+  CodeStore<BITS, R, NA>& cs = reinterpret_cast<CodeStore<BITS, R, NA>*>(smem)[wave];
+  for (int i = threadIdx.x; i < p.n_vis_all; i += 64 * NW) {
+    vis_lds[2 * i] = p.vis_slot[i];
+    vis_lds[2 * i + 1] = p.vis_mask[i];
+  }
+  __syncthreads();
+
   f32x4 acc_base[R][TT], acc_raw[R][TT];
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt)
@@ -402,20 +445,38 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // This wavefront's steps are s_begin + wave + NW j, j < cnt, visited from a start that differs from row
   // group to row group, so that workgroups running side by side stream from different places of their rows
   // instead of marching through addresses a large power of two apart in lockstep.  The step after the last
-  // is prefetched again from the last (a harmless reload).
+  // is prefetched again from the last (a harmless reload).  All loads are unconditional and in a fixed
+  // order, so the compiler can wait for exactly the ones a computation needs while younger ones fly.
   {
     const int len = s_end - s_begin;
     const int cnt = len > wave ? (len - wave + NW - 1) / NW : 0;
     if (cnt > 0) {
       const int rot = (int)(((uint32_t)rg * 2654435761u) >> 8) % cnt;
       auto step_of = [&](int j) { j = j < cnt ? j : cnt - 1; int r = j + rot; r = r >= cnt ? r - cnt : r; return s_begin + wave + NW * r; };
-      StepBuf<BITS, R, TT, NA> bufA, bufB;
-      load_step<BITS, R, TT, NA>(p, step_of(0), lane, jt0, n_steps, bufA);
+      u32x4 base[R][C::NM];
+      uint32_t cw[NA][R][C::PLANES];
+      ActBuf<BITS, TT> xa, xb;
+      load_act<BITS, TT>(p, step_of(0), lane, xa);
+      load_base<BITS, R>(p, step_of(0), lane, jt0, base);
+      load_codes<BITS, R, NA>(p, step_of(0), lane, jt0, n_steps, cw);
+      auto one_step = [&](int j, ActBuf<BITS, TT>& xcur, ActBuf<BITS, TT>& xnext) {
+        // park this step's code words in LDS, then put the next step's loads in flight
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+            for (int pl = 0; pl < C::PLANES; ++pl) cs.w[a][rt][pl][lane] = cw[a][rt][pl];
+        const int s = step_of(j), sn = step_of(j + 1);
+        if (XDB) load_act<BITS, TT>(p, sn, lane, xnext);
+        load_codes<BITS, R, NA>(p, sn, lane, jt0, n_steps, cw);
+        compute_step<BITS, R, TT, NA>(p, s, sn, lane, jt0, n_steps, base, xcur, cs, vis_lds, acc_base, acc_raw);
+        if (!XDB) load_act<BITS, TT>(p, sn, lane, xcur);
+      };
       for (int j = 0; j < cnt; j += 2) {
-        load_step<BITS, R, TT, NA>(p, step_of(j + 1), lane, jt0, n_steps, bufB);
-        compute_step<BITS, R, TT, NA>(p, step_of(j), lane, jt0, n_steps, bufA, acc_base, acc_raw);
-        load_step<BITS, R, TT, NA>(p, step_of(j + 2), lane, jt0, n_steps, bufA);
-        if (j + 1 < cnt) compute_step<BITS, R, TT, NA>(p, step_of(j + 1), lane, jt0, n_steps, bufB, acc_base, acc_raw);
+        one_step(j, xa, XDB ? xb : xa);
+        if (j + 1 >= cnt) break;
+        one_step(j + 1, XDB ? xb : xa, xa);
       }
     }
   }
@@ -445,7 +506,8 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   }
 
   // epilogue: remove biases / zero point, apply the expert's step, add across wavefronts
-  __shared__ float red[NW][R * TT * 4][64];
+  __syncthreads();   // the reduction buffer reuses the code-word storage
+  float (*red)[R * TT * 4][64] = reinterpret_cast<float (*)[R * TT * 4][64]>(smem);
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     const int tl = 16 * tt + n;
@@ -506,18 +568,20 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const LinearParams p, int
   *reinterpret_cast<uint2*>(p.y + (size_t)(p.t0 + tl) * p.d_out + j) = pk;
 }
 
+constexpr int kRowsPerGroup = 32;   // two 16-row tiles per wavefront
+constexpr int kWaves = 4;           // wavefronts per workgroup; they split the workgroup's columns
+
 struct Plan {
-  int nsplit;  // workgroups that share one row tile's columns
+  int nsplit;  // workgroups that share one row group's columns
 };
 
-// Pure function of the layer shape (not of bits or T), so the workspace size is known up front.
-// One 16-row tile per workgroup; columns are split over workgroups only when there are fewer row
-// tiles than compute units.
+// Pure function of the layer shape (not of bits or T), so the workspace size is known up front.  Two
+// workgroups fit a compute unit; columns are split over workgroups until there are about two per unit.
 Plan plan_for(int d_in, int d_out) {
   const int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
   const int n_chunks = pi / 128;
-  const int row_tiles = po / 16;
-  int ns = (256 + row_tiles - 1) / row_tiles;
+  const int row_groups = po / kRowsPerGroup;
+  int ns = (512 + row_groups - 1) / row_groups;
   const int max_split = n_chunks / 8 > 0 ? n_chunks / 8 : 1;   // at least eight 128-column chunks per workgroup
   if (ns > max_split) ns = max_split;
   if (ns < 1) ns = 1;
@@ -545,8 +609,7 @@ WorkspaceLayout workspace_layout(int d_in, int d_out) {
 
 template <int BITS, int TT, int NA>
 hipError_t launch_main(const LinearParams& p, dim3 grid, hipStream_t s) {
-  constexpr int NW = BITS == 2 ? 8 : 4;
-  k_delta_linear<BITS, 1, TT, NA, NW><<<grid, 64 * NW, 0, s>>>(p);
+  k_delta_linear<BITS, kRowsPerGroup / 16, TT, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p);
   return hipGetLastError();
 }
 
@@ -599,13 +662,13 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.nsplit = pl.nsplit;
   p.bits = d0.bits;
   p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
-  const dim3 grid(po / 16, pl.nsplit);
+  const dim3 grid(po / kRowsPerGroup, pl.nsplit);
   for (int t0 = 0; t0 < c.T; t0 += kTokGroup) {
     p.t0 = t0;
     const int nt = c.T - t0 < kTokGroup ? c.T - t0 : kTokGroup;
     const int tt = (nt + 15) / 16;
-    // active slots: the experts that own tokens of this group, in expert order; visits: their token tiles
-    int na = 0, nv = 0;
+    // active slots: the experts that own tokens of this group, in expert order
+    int na = 0;
     for (int e = 0; e < c.n_experts; ++e) {
       const int lo = (c.seg[e] > t0 ? c.seg[e] : t0) - t0;
       const int hi = (c.seg[e + 1] < t0 + nt ? c.seg[e + 1] : t0 + nt) - t0;
@@ -616,14 +679,31 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       p.sidx[na] = c.experts[e].salient_idx;
       p.lo[na] = (int16_t)lo;
       p.hi[na] = (int16_t)hi;
-      for (int t = lo / 16; t <= (hi - 1) / 16; ++t) { p.vis_slot[nv] = (uint8_t)na; p.vis_tt[nv] = (uint8_t)t; ++nv; }
       ++na;
     }
     for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional prefetches stay valid
       p.codes[a] = p.codes[0]; p.step[a] = p.step[0]; p.sal[a] = p.sal[0]; p.sidx[a] = p.sidx[0];
       p.lo[a] = 0; p.hi[a] = 0;
     }
-    for (int v = nv; v <= kMaxVisits; ++v) { p.vis_slot[v] = 0; p.vis_tt[v] = 0; }
+    // visits, tile-major: for every 16-token tile the slots that own tokens in it, with the tile's token mask
+    int nv = 0;
+    for (int t = 0; t < 4; ++t) {
+      p.tile_beg[t] = nv;
+      for (int a = 0; a < na; ++a) {
+        const int l = p.lo[a] > 16 * t ? p.lo[a] : 16 * t;
+        const int h = p.hi[a] < 16 * t + 16 ? p.hi[a] : 16 * t + 16;
+        if (h <= l) continue;
+        uint32_t m16 = 0;
+        for (int n = l - 16 * t; n < h - 16 * t; ++n) m16 |= 1u << n;
+        p.vis_slot[nv] = (uint8_t)a;
+        p.vis_tt[nv] = (uint8_t)t;
+        p.vis_mask[nv] = m16 | (m16 << 16);
+        ++nv;
+      }
+    }
+    p.tile_beg[4] = nv;
+    for (int v = nv; v <= kMaxVisits; ++v) { p.vis_slot[v] = 0; p.vis_tt[v] = 0; p.vis_mask[v] = 0; }
+    p.n_vis_all = nv;
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
     k_prepare<<<p.n_kb + p.n_vis + kTokGroup, 256, 0, s>>>(p);
