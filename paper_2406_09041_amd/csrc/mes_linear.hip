@@ -232,9 +232,15 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
   double acc = 0.0;
   if (t < p.T) {
     const uint16_t* xrow = p.x + (size_t)t * p.d_in;
-    for (int c = tid; c < p.d_in; c += 256) {
-      const double xv = (double)bf16_to_f32(xrow[c]);
-      acc += xv * ((double)bias_of_column(p.bits, c) + (double)p.z);
+    for (int c8 = tid; c8 < p.d_in / 8; c8 += 256) {   // eight columns (four bias pairs) per 16-byte load
+      const u32x4 v = *reinterpret_cast<const u32x4*>(xrow + 8 * c8);
+      float part = 0.0f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float bz = bias_of_column(p.bits, 8 * c8 + 2 * q) + p.z;
+        part += (bf16_to_f32((uint16_t)(v[q] & 0xffffu)) + bf16_to_f32((uint16_t)(v[q] >> 16))) * bz;
+      }
+      acc += (double)part;
     }
     int a = -1;
     for (int s = 0; s < p.n_act; ++s)
@@ -352,14 +358,37 @@ struct CodeStore {
   uint32_t w[NA][R][Codec<BITS>::PLANES][64];
 };
 
+// Code words of `slot` for this lane: from the wavefront's LDS store, or straight from memory when the group
+// has more active experts than prefetch slots (> 16 experts inside one 64-token group).
+template <int BITS, int R, int NA>
+__device__ __forceinline__ void fetch_codes(const LinearParams& p, uint32_t slot, int s, int lane, int jt0, int n_steps,
+                                            const CodeStore<BITS, R, NA>& cs, uint32_t (&cw)[R][Codec<BITS>::PLANES]) {
+  using C = Codec<BITS>;
+  if (slot < (uint32_t)NA) {
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt)
+#pragma unroll
+      for (int pl = 0; pl < C::PLANES; ++pl) cw[rt][pl] = cs.w[slot][rt][pl][lane];
+  } else {
+#pragma unroll
+    for (int rt = 0; rt < R; ++rt) {
+      const char* src = reinterpret_cast<const char*>(p.codes[slot]) + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 256);
+#pragma unroll
+      for (int pl = 0; pl < C::PLANES; ++pl) cw[rt][pl] = ld32(src + pl * 256, (uint32_t)lane * 4u);
+    }
+  }
+}
+
 // Arithmetic of one step.  Token tiles are walked in a fixed (unrolled) order; the experts that have tokens
-// in a tile are walked by a plain loop over the host-built visit table, whose body has no branch: read the
-// expert's code words from LDS, dequantise, zero the lanes of other experts' tokens, accumulate.
+// in a tile are walked by a plain loop over the host-built visit table, whose body has no branch around an
+// accumulator: dequantise the expert's code words, zero the lanes of other experts' tokens, accumulate.
+// The visit table lives in two vector registers (lane v = visit v: slot, token mask) and is read with
+// v_readlane; the code words of the next visit are fetched from LDS while the current visit is multiplied.
 template <int BITS, int R, int TT, int NA>
 __device__ __forceinline__ void compute_step(const LinearParams& p, int s, int s_next, int lane, int jt0, int n_steps,
                                              u32x4 (&base)[R][Codec<BITS>::NM], const ActBuf<BITS, TT>& x,
-                                             const CodeStore<BITS, R, NA>& cs, const uint32_t* vis_lds,
-                                             f32x4 (&acc_base)[R][TT], f32x4 (&acc_raw)[R][TT]) {
+                                             const CodeStore<BITS, R, NA>& cs, const uint32_t (&vslot)[2],
+                                             const uint32_t (&vmask)[2], f32x4 (&acc_base)[R][TT], f32x4 (&acc_raw)[R][TT]) {
   using C = Codec<BITS>;
 #pragma unroll
   for (int m = 0; m < C::NM; ++m)
@@ -368,40 +397,31 @@ __device__ __forceinline__ void compute_step(const LinearParams& p, int s, int s
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) acc_base[rt][tt] = mfma16(base[rt][m], x.xb[tt][m], acc_base[rt][tt]);
   load_base<BITS, R>(p, s_next, lane, jt0, base);   // reloaded in place for the next step, a full step ahead
+  auto desc = [&](const uint32_t (&tab)[2], int v) {
+    return v < 64 ? __builtin_amdgcn_readlane(tab[0], v) : __builtin_amdgcn_readlane(tab[1], v - 64);
+  };
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
-    const int v_end = p.tile_beg[tt + 1];
-    for (int v = p.tile_beg[tt]; v < v_end; ++v) {
-      // visit descriptor: slot and the 16-bit token mask of the tile, replicated over the four lane groups
-      const uint32_t slot = __builtin_amdgcn_readfirstlane(vis_lds[2 * v]);
-      const uint32_t m16 = __builtin_amdgcn_readfirstlane(vis_lds[2 * v + 1]);
-      const uint64_t lane_mask = ((uint64_t)m16 << 32) | m16;
-      u32x4 dq[R][C::NM];
-      if (slot < (uint32_t)NA) {
+    const int v_beg = p.tile_beg[tt], v_end = p.tile_beg[tt + 1];
+    if (v_beg < v_end) {
+      uint32_t cw[R][C::PLANES];
+      fetch_codes<BITS, R, NA>(p, desc(vslot, v_beg), s, lane, jt0, n_steps, cs, cw);
+      for (int v = v_beg; v < v_end; ++v) {
+        const uint32_t m16 = desc(vmask, v);
+        const uint64_t lane_mask = ((uint64_t)m16 << 32) | m16;
+        u32x4 dq[R][C::NM];
 #pragma unroll
-        for (int rt = 0; rt < R; ++rt) {
-          uint32_t cw[C::PLANES];
+        for (int rt = 0; rt < R; ++rt) C::dequant(cw[rt], dq[rt]);
+        const int vn = v + 1 < v_end ? v + 1 : v;
+        fetch_codes<BITS, R, NA>(p, desc(vslot, vn), s, lane, jt0, n_steps, cs, cw);   // next visit's words
 #pragma unroll
-          for (int pl = 0; pl < C::PLANES; ++pl) cw[pl] = cs.w[slot][rt][pl][lane];
-          C::dequant(cw, dq[rt]);
+        for (int m = 0; m < C::NM; ++m) {
+          u32x4 xm;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) xm[q] = keep_if(x.xb[tt][m][q], lane_mask);
+#pragma unroll
+          for (int rt = 0; rt < R; ++rt) acc_raw[rt][tt] = mfma16(dq[rt][m], xm, acc_raw[rt][tt]);
         }
-      } else {   // more active experts than prefetch slots (> 16 experts inside one 64-token group): load on demand
-#pragma unroll
-        for (int rt = 0; rt < R; ++rt) {
-          uint32_t cw[C::PLANES];
-          const char* src = reinterpret_cast<const char*>(p.codes[slot]) + ((size_t)(jt0 + rt) * n_steps + s) * (C::PLANES * 256);
-#pragma unroll
-          for (int pl = 0; pl < C::PLANES; ++pl) cw[pl] = ld32(src + pl * 256, (uint32_t)lane * 4u);
-          C::dequant(cw, dq[rt]);
-        }
-      }
-#pragma unroll
-      for (int m = 0; m < C::NM; ++m) {
-        u32x4 xm;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) xm[q] = keep_if(x.xb[tt][m][q], lane_mask);
-#pragma unroll
-        for (int rt = 0; rt < R; ++rt) acc_raw[rt][tt] = mfma16(dq[rt][m], xm, acc_raw[rt][tt]);
       }
     }
   }
@@ -428,13 +448,15 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   constexpr int kCodeBytes = (int)sizeof(CodeStore<BITS, R, NA>) * NW;
   constexpr int kRedBytes = NW * R * TT * 4 * 64 * 4;
   __shared__ __attribute__((aligned(16))) char smem[kCodeBytes > kRedBytes ? kCodeBytes : kRedBytes];
-  __shared__ uint32_t vis_lds[2 * (kMaxVisits + 1)];
   CodeStore<BITS, R, NA>& cs = reinterpret_cast<CodeStore<BITS, R, NA>*>(smem)[wave];
-  for (int i = threadIdx.x; i < p.n_vis_all; i += 64 * NW) {
-    vis_lds[2 * i] = p.vis_slot[i];
-    vis_lds[2 * i + 1] = p.vis_mask[i];
+  // visit table in registers: lane v (and lane v - 64 of the second register) holds visit v
+  uint32_t vslot[2], vmask[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int v = 64 * h + lane;
+    vslot[h] = v <= kMaxVisits ? p.vis_slot[v] : 0;
+    vmask[h] = v <= kMaxVisits ? p.vis_mask[v] : 0;
   }
-  __syncthreads();
 
   f32x4 acc_base[R][TT], acc_raw[R][TT];
 #pragma unroll
@@ -470,7 +492,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
         const int s = step_of(j), sn = step_of(j + 1);
         if (XDB) load_act<BITS, TT>(p, sn, lane, xnext);
         load_codes<BITS, R, NA>(p, sn, lane, jt0, n_steps, cw);
-        compute_step<BITS, R, TT, NA>(p, s, sn, lane, jt0, n_steps, base, xcur, cs, vis_lds, acc_base, acc_raw);
+        compute_step<BITS, R, TT, NA>(p, s, sn, lane, jt0, n_steps, base, xcur, cs, vslot, vmask, acc_base, acc_raw);
         if (!XDB) load_act<BITS, TT>(p, sn, lane, xcur);
       };
       for (int j = 0; j < cnt; j += 2) {
