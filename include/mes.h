@@ -24,27 +24,26 @@
  *    HIP call.
  *  - Shapes: d_in % 8 == 0 and d_out % 4 == 0 (row starts of x / y stay 16-byte /
  *    8-byte aligned).  Stored matrices are zero padded to d_out_pad = ceil64(d_out),
- *    d_in_pad = ceil512(d_in), k_pad = ceil32(k).
+ *    d_in_pad = ceil128(d_in), k_pad = ceil32(k).
  *
  * Storage layouts (tile-major, so that one 64-lane wavefront reads contiguous
  * memory and holds a matrix-core operand without any shuffle).  A "lane slot" is
- * lane = 16 g + r: r = row inside a 16-row tile, g = which run of 8 consecutive
- * columns inside a 32-column block.
+ * lane = 16 g + r: r = row inside a 16-row tile, g = one of four column groups.
  *  - base:    uint16 (bf16 bits) [d_out_pad/16][d_in_pad/32][64 lanes][8];
  *             slot (jt, kb, lane, e) holds W[16 jt + r][32 kb + 8 g + e].
  *  - salient: uint16 (fp16 bits) [d_out_pad/16][k_pad/32][64][8];
  *             slot (jt, sb, lane, e) holds fp16(Delta[16 jt + r][S[32 sb + 8 g + e]]).
- *  - codes:   uint32 [d_out_pad/16][d_in_pad/KSTEP][planes][64 lanes], KSTEP = 64
- *             (b = 2) or 128 (b = 1, 3); the lane's words hold the codes of row
- *             16 jt + r at columns KSTEP ks + 32 m + 8 g + 2 q + h
- *             (m < KSTEP/32, q < 4, h < 2):
- *               b = 2: one word; code at bits [16 h + 2 (4 m + q), +2).
- *               b = 1: one word; code at bit   16 h + (4 m + q).
- *               b = 3: three words.  Word 0: low two code bits for m in {0,1} at
- *                      bits [16 h + 2 p, +2), p = 4 m + q.  Word 1: the same for
- *                      m in {2,3}, p = 4 (m - 2) + q.  Word 2: the high code bit;
- *                      for m < 2 at bit 16 h + (p <= 6 ? 2 p + 2 : 0), for m >= 2 at
- *                      bit 16 h + 2 p + 1.
+ *  - codes:   blocks of 32 rows x 128 columns, [d_out_pad/32][d_in_pad/128], 512 b
+ *             bytes each.  Inside block (jp, c) the lane 16 g + r owns, for each of its
+ *             two row tiles rt (row = 32 jp + 16 rt + r), the 32 columns
+ *             128 c + 32 g + e, e = 8 q + p (q < 4, p < 8).  Codes sit in 4-bit fields
+ *             (field p of a 32-bit word = bits [4 p, 4 p + 4)) so that one AND turns a
+ *             word into eight fp4 (E2M1) matrix-core inputs:
+ *               b = 1: uint32 [64 lanes][2 rt]; code of element (q, p) at bit 4 p + q.
+ *               b = 2: uint32 [64 lanes][2 rt][2 w]; code of element (q, p) in word
+ *                      w = q / 2 at bits [4 p + 2 (q % 2), + 2).
+ *               b = 3: the b = 2 block holding the low two code bits (1024 bytes),
+ *                      followed by a b = 1 block holding the high code bit (512 bytes).
  *             Codes of salient columns, padding columns and padding rows are 0.
  *    The code u is unsigned; the weight it stands for is (u - z) * step[row] with
  *    z = 2^(b-1) - 1/2 (MES_GRID_SYM) or 2^(b-1) (MES_GRID_EQ1, Eq. 1's levels).
@@ -80,7 +79,7 @@ enum { MES_GRID_SYM = 0, MES_GRID_EQ1 = 1 };
 enum { MES_STEP_GIVEN = 0, MES_STEP_MAXABS = 1, MES_STEP_MEANABS = 2 };
 
 #define MES_MAX_EXPERTS 64
-#define MES_LAYOUT_VERSION 1
+#define MES_LAYOUT_VERSION 2
 
 /* One expert's compressed delta for one linear layer (all pointers DEVICE, caller-owned). */
 typedef struct {

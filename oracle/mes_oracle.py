@@ -214,11 +214,11 @@ def select_salient(delta32, x_calib32, bits, grid, k, policy: int = STEP_MAXABS)
 # ------------------------------------------------------------------------------------------------
 # Storage layouts of the library (its own definition; written here from the layout specification,
 # not from the kernels).  A "lane slot" is lane = 16 * g + r: r = row inside a 16-row tile,
-# g = which run of 8 consecutive columns inside a 32-column block.
+# g = one of four column groups.
 # ------------------------------------------------------------------------------------------------
 
 ROW_PAD = 64
-COL_PAD = 512
+COL_PAD = 128
 SAL_PAD = 32
 
 
@@ -269,46 +269,35 @@ def unpack_salient(t: np.ndarray, d_out: int, k: int) -> np.ndarray:
     return _untile_16x32(t)[:d_out, :k].copy().view(np.float16)
 
 
-def _code_bit_positions(bits: int):
-    """Where the code of column (m, q, h) of a lane's run sits.
+def _nibble_words(field: np.ndarray, width: int) -> np.ndarray:
+    """field uint32 [..., 4 q, 8 p] -> words [..., 4 // (4 // width)]: `width`-bit fields, 4 // width of them
+    stacked inside each 4-bit field p (element q % (4 // width) at bit offset width * that), word q // (4 // width)."""
+    per = 4 // width                       # elements q sharing one word
+    lead = field.shape[:-2]
+    words = np.zeros(lead + (4 // per,), dtype=np.uint32)
+    for q in range(4):
+        for p in range(8):
+            words[..., q // per] |= field[..., q, p] << np.uint32(4 * p + width * (q % per))
+    return words
 
-    A lane slot owns, inside one K-step (64 columns for b = 2, 128 for b = 1 and b = 3),
-    the columns 32 m + 8 g + 2 q + h.  Returns (n_m, n_planes, [(plane, m, q, h, shift, field_mask, code_shift)]):
-    the stored bits are ((code >> code_shift) & field_mask) << shift in dword `plane`.
-    """
-    out = []
-    if bits == 2:
-        for m in range(2):
-            for q in range(4):
-                for h in range(2):
-                    out.append((0, m, q, h, 16 * h + 2 * (4 * m + q), 3, 0))
-        return 2, 1, out
-    if bits == 1:
-        for m in range(4):
-            for q in range(4):
-                for h in range(2):
-                    out.append((0, m, q, h, 16 * h + (4 * m + q), 1, 0))
-        return 4, 1, out
-    if bits == 3:
-        for m in range(4):
-            for q in range(4):
-                for h in range(2):
-                    p = 4 * (m % 2) + q
-                    plane = 0 if m < 2 else 1
-                    out.append((plane, m, q, h, 16 * h + 2 * p, 3, 0))       # low two bits
-                    if m < 2:
-                        cpos = 2 * p + 2 if p <= 6 else 0
-                    else:
-                        cpos = 2 * p + 1
-                    out.append((2, m, q, h, 16 * h + cpos, 1, 2))            # high bit
-        return 4, 3, out
-    raise ValueError("bits")
+
+def _unnibble_words(words: np.ndarray, width: int) -> np.ndarray:
+    per = 4 // width
+    lead = words.shape[:-1]
+    field = np.zeros(lead + (4, 8), dtype=np.uint32)
+    for q in range(4):
+        for p in range(8):
+            field[..., q, p] = (words[..., q // per] >> np.uint32(4 * p + width * (q % per))) & np.uint32((1 << width) - 1)
+    return field
 
 
 def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
-    """Logical codes uint8 [d_out, d_in] (0xFF = salient) -> uint32 [d_out_pad/16, d_in_pad/kstep, planes, 64].
+    """Logical codes uint8 [d_out, d_in] (0xFF = salient) -> uint32 [d_out_pad/32, d_in_pad/128, 128 * bits].
 
-    Salient columns, padding columns and padding rows store code 0.
+    Blocks of 32 rows x 128 columns.  Lane 16 g + r owns, for each of its two row tiles rt, the 32 columns
+    32 g + 8 q + p.  b = 1: words [lane][rt], code at bit 4 p + q.  b = 2: words [lane][rt][w], code of (q, p)
+    in word q // 2 at bits 4 p + 2 (q % 2).  b = 3: the b = 2 block of the low two bits, then the b = 1 block
+    of the high bit.  Salient columns, padding columns and padding rows store code 0.
     """
     d_out, d_in = codes.shape
     po, pi, _ = padded_dims(d_out, d_in)
@@ -316,27 +305,29 @@ def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
     c = codes.astype(np.uint32)
     c[codes == SALIENT_MARK] = 0
     u[:d_out, :d_in] = c
-    n_m, planes, table = _code_bit_positions(bits)
-    kstep = 32 * n_m
-    v = u.reshape(po // 16, 16, pi // kstep, n_m, 4, 4, 2)      # jt, r, ks, m, g, q, h
-    out = np.zeros((po // 16, pi // kstep, planes, 4, 16), dtype=np.uint32)   # jt, ks, plane, g, r
-    for plane, m, q, h, shift, mask, cshift in table:
-        field = (v[:, :, :, m, :, q, h] >> np.uint32(cshift)) & np.uint32(mask)   # jt, r, ks, g
-        out[:, :, plane] |= (field << np.uint32(shift)).transpose(0, 2, 3, 1)
-    return out.reshape(po // 16, pi // kstep, planes, 64)
+    v = u.reshape(po // 32, 2, 16, pi // 128, 4, 4, 8)          # jp, rt, r, c, g, q, p
+    v = v.transpose(0, 3, 4, 2, 1, 5, 6)                         # jp, c, g, r, rt, q, p
+    v = v.reshape(po // 32, pi // 128, 64, 2, 4, 8)              # jp, c, lane, rt, q, p
+    if bits == 1:
+        return _nibble_words(v, 1).reshape(po // 32, pi // 128, 128)
+    low = _nibble_words(v & np.uint32(3), 2).reshape(po // 32, pi // 128, 256)
+    if bits == 2:
+        return low
+    high = _nibble_words(v >> np.uint32(2), 1).reshape(po // 32, pi // 128, 128)
+    return np.concatenate([low, high], axis=2)
 
 
 def unpack_codes(packed: np.ndarray, bits: int, d_out: int, d_in: int) -> np.ndarray:
     """Inverse of pack_codes (salient columns come back as code 0)."""
-    n_m, planes, table = _code_bit_positions(bits)
-    kstep = 32 * n_m
-    njt, nks = packed.shape[0], packed.shape[1]
-    p = packed.reshape(njt, nks, planes, 4, 16)
-    v = np.zeros((njt, 16, nks, n_m, 4, 4, 2), dtype=np.uint32)
-    for plane, m, q, h, shift, mask, cshift in table:
-        field = (p[:, :, plane] >> np.uint32(shift)) & np.uint32(mask)            # jt, ks, g, r
-        v[:, :, :, m, :, q, h] |= (field << np.uint32(cshift)).transpose(0, 3, 1, 2)
-    return v.reshape(njt * 16, nks * kstep)[:d_out, :d_in].astype(np.uint8)
+    njp, nc = packed.shape[0], packed.shape[1]
+    if bits == 1:
+        v = _unnibble_words(packed.reshape(njp, nc, 64, 2, 1), 1)
+    else:
+        v = _unnibble_words(packed[:, :, :256].reshape(njp, nc, 64, 2, 2), 2)
+        if bits == 3:
+            v = v | (_unnibble_words(packed[:, :, 256:].reshape(njp, nc, 64, 2, 1), 1) << np.uint32(2))
+    v = v.reshape(njp, nc, 4, 16, 2, 4, 8).transpose(0, 4, 3, 1, 2, 5, 6)   # jp, rt, r, c, g, q, p
+    return np.ascontiguousarray(v).reshape(njp * 32, nc * 128)[:d_out, :d_in].astype(np.uint8)
 
 
 def codes_bytes(d_in: int, d_out: int, bits: int) -> int:

@@ -10,13 +10,11 @@
 namespace mes {
 
 constexpr int kRowPad = 64;    // stored rows are padded to a multiple of this
-constexpr int kColPad = 512;   // stored columns are padded to a multiple of this
+constexpr int kColPad = 128;   // stored columns are padded to a multiple of this (one chunk)
 constexpr int kSalPad = 32;    // stored salient columns are padded to a multiple of this
 constexpr int kTokGroup = 64;  // tokens one decode launch covers
 
 inline int ceil_to(int n, int m) { return (n + m - 1) / m * m; }
-inline int kstep_of(int bits) { return bits == 2 ? 64 : 128; }
-inline int planes_of(int bits) { return bits == 3 ? 3 : 1; }
 
 // Error plumbing (thread-local message, see mes_last_error()).
 mes_status fail(mes_status st, const char* fmt, ...);

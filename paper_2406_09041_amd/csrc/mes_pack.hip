@@ -115,48 +115,57 @@ __global__ void k_row_step(const float* __restrict__ delta, int d_in, const int3
   }
 }
 
-// Bit position of the high code bit in word 2 of the 3-bit layout.
-__device__ __forceinline__ int hi_pos3(int m, int q) {
-  int p = 4 * (m & 1) + q;
-  return m < 2 ? (p <= 6 ? 2 * p + 2 : 0) : 2 * p + 1;
+// Where the code of (row, col) is stored (see mes.h, "codes").  Blocks of 32 rows x 128 columns; inside a
+// block lane = 16 g + r owns, for each of its two 16-row tiles rt, the 32 columns 32 g + e, e = 8 q + pp.
+struct CodeLoc {
+  size_t lo_word;   // index of the 32-bit word holding the low bits (all bits for b = 1, 2)
+  int lo_shift;
+  size_t hi_word;   // b = 3: word holding the high bit
+  int hi_shift;
+};
+
+__device__ __forceinline__ CodeLoc code_location(int bits, int n_chunks, int row, int col) {
+  const int jp = row >> 5, rt = (row >> 4) & 1, r = row & 15;
+  const int c = col >> 7, g = (col >> 5) & 3, e = col & 31, q = e >> 3, pp = e & 7;
+  const int lane = 16 * g + r;
+  const size_t blk = ((size_t)jp * n_chunks + c) * (bits == 1 ? 128 : bits == 2 ? 256 : 384);
+  CodeLoc L;
+  if (bits == 1) {
+    L.lo_word = blk + lane * 2 + rt;
+    L.lo_shift = 4 * pp + q;
+    L.hi_word = 0; L.hi_shift = 0;
+  } else {
+    L.lo_word = blk + lane * 4 + rt * 2 + (q >> 1);
+    L.lo_shift = 4 * pp + 2 * (q & 1);
+    L.hi_word = blk + 256 + lane * 2 + rt;
+    L.hi_shift = 4 * pp + q;
+  }
+  return L;
 }
 
-// One thread per stored code word.
+// One thread per (row, 8 consecutive columns): quantise and OR the codes into their words (the buffer was
+// zeroed before; words are shared by threads, hence atomicOr).
 __global__ void k_pack_codes(const float* __restrict__ delta, int d_in, int d_out, const int32_t* __restrict__ sidx,
-                             int k, int bits, int grid, const float* __restrict__ step, int n_ks, size_t n_words,
+                             int k, int bits, int grid, const float* __restrict__ step, int n_chunks,
                              uint32_t* __restrict__ out) {
-  size_t widx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (widx >= n_words) return;
-  const int planes = bits == 3 ? 3 : 1;
-  const int n_m = bits == 2 ? 2 : 4;
-  const int kstep = 32 * n_m;
-  int lane = (int)(widx & 63);
-  size_t rest = widx >> 6;
-  int plane = (int)(rest % planes); rest /= planes;
-  int ks = (int)(rest % n_ks);
-  int jt = (int)(rest / n_ks);
-  int row = 16 * jt + (lane & 15);
-  int g = lane >> 4;
-  uint32_t word = 0;
-  if (row < d_out) {
-    const float s = step[row];
-    const float* r = delta + (size_t)row * d_in;
-    for (int m = 0; m < n_m; ++m) {
-      if (bits == 3 && plane == 0 && m >= 2) continue;
-      if (bits == 3 && plane == 1 && m < 2) continue;
-      for (int q = 0; q < 4; ++q)
-        for (int h = 0; h < 2; ++h) {
-          int col = kstep * ks + 32 * m + 8 * g + 2 * q + h;
-          if (col >= d_in || is_salient(sidx, k, col, nullptr)) continue;
-          uint32_t u = quant_code(r[col], s, bits, grid);
-          if (bits == 2) word |= u << (16 * h + 2 * (4 * m + q));
-          else if (bits == 1) word |= u << (16 * h + (4 * m + q));
-          else if (plane < 2) word |= (u & 3u) << (16 * h + 2 * (4 * (m & 1) + q));
-          else word |= (u >> 2) << (16 * h + hi_pos3(m, q));
-        }
-    }
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int groups = d_in / 8;
+  if (idx >= (size_t)d_out * groups) return;
+  const int row = (int)(idx / groups), col0 = (int)(idx % groups) * 8;
+  const float s = step[row];
+  const float* r = delta + (size_t)row * d_in;
+  uint32_t lo_bits = 0, hi_bits = 0;
+  const CodeLoc L0 = code_location(bits, n_chunks, row, col0);   // the 8 columns share both words
+  for (int pp = 0; pp < 8; ++pp) {
+    const int col = col0 + pp;
+    if (is_salient(sidx, k, col, nullptr)) continue;
+    const uint32_t u = quant_code(r[col], s, bits, grid);
+    const CodeLoc L = code_location(bits, n_chunks, row, col);
+    lo_bits |= (bits == 3 ? (u & 3u) : u) << L.lo_shift;
+    if (bits == 3) hi_bits |= (u >> 2) << L.hi_shift;
   }
-  out[widx] = word;
+  if (lo_bits) atomicOr(out + L0.lo_word, lo_bits);
+  if (bits == 3 && hi_bits) atomicOr(out + L0.hi_word, hi_bits);
 }
 
 // `flag` was written by k_check_salient earlier on the same stream: with indices that failed the check
@@ -183,19 +192,12 @@ __global__ void k_pack_salient(const float* __restrict__ delta, int d_in, int d_
   out[idx] = v;
 }
 
-__device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, int n_ks, int row, int col) {
-  const int n_m = bits == 2 ? 2 : 4;
-  const int kstep = 32 * n_m;
-  const int planes = bits == 3 ? 3 : 1;
-  int jt = row >> 4, r = row & 15;
-  int ks = col / kstep, c = col % kstep;
-  int m = c >> 5, g = (c >> 3) & 3, q = (c >> 1) & 3, h = c & 1;
-  const uint32_t* w = codes + ((size_t)(jt * n_ks + ks) * planes) * 64 + (16 * g + r);
-  if (bits == 2) return (w[0] >> (16 * h + 2 * (4 * m + q))) & 3u;
-  if (bits == 1) return (w[0] >> (16 * h + (4 * m + q))) & 1u;
-  uint32_t lo = (w[(m < 2 ? 0 : 1) * 64] >> (16 * h + 2 * (4 * (m & 1) + q))) & 3u;
-  uint32_t hi = (w[2 * 64] >> (16 * h + hi_pos3(m, q))) & 1u;
-  return lo | (hi << 2);
+__device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, int n_chunks, int row, int col) {
+  const CodeLoc L = code_location(bits, n_chunks, row, col);
+  if (bits == 1) return (codes[L.lo_word] >> L.lo_shift) & 1u;
+  const uint32_t lo = (codes[L.lo_word] >> L.lo_shift) & 3u;
+  if (bits == 2) return lo;
+  return lo | (((codes[L.hi_word] >> L.hi_shift) & 1u) << 2);
 }
 
 __global__ void k_unpack_delta(const uint32_t* __restrict__ codes, const float* __restrict__ step,
@@ -302,9 +304,9 @@ hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int3
   k_row_step<<<d_out, 256, 0, s>>>(delta, d_in, sidx, k, bits, grid, policy, step_in, step_out);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
-  int n_ks = pi / kstep_of(bits);
-  size_t n_words = (size_t)(po / 16) * n_ks * planes_of(bits) * 64;
-  k_pack_codes<<<blocks_for(n_words, 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, bits, grid, step_out, n_ks, n_words, codes);
+  const int n_chunks = pi / 128;
+  if ((e = launch_fill_zero(codes, (size_t)po * pi * bits / 8, s)) != hipSuccess) return e;
+  k_pack_codes<<<blocks_for((size_t)d_out * (d_in / 8), 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, bits, grid, step_out, n_chunks, codes);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (k > 0) {
     int n_sb = ceil_to(k, kSalPad) / 32;
@@ -317,7 +319,7 @@ hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int3
 
 hipError_t launch_unpack_delta(const mes_delta& d, float* delta_hat, uint8_t* codes_out, hipStream_t s) {
   int pi = ceil_to(d.d_in, kColPad);
-  int n_ks = pi / kstep_of(d.bits);
+  int n_ks = pi / 128;
   int n_sb = ceil_to(d.k, kSalPad) / 32;
   size_t n = (size_t)d.d_in * d.d_out;
   k_unpack_delta<<<blocks_for(n, 256), 256, 0, s>>>(reinterpret_cast<const uint32_t*>(d.codes), d.step,

@@ -42,33 +42,62 @@ def test_pack_unpack_roundtrip(bits, shape):
 
 @pytest.mark.parametrize("bits", [1, 2, 3])
 def test_pack_every_bit_is_used_exactly_once(bits):
-    """One-hot probes: each (column, code bit) lands on its own bit of the packed words, none collide."""
-    n_m = {1: 4, 2: 2, 3: 4}[bits]
-    kstep = 32 * n_m
+    """One-hot probes: each (row tile, column, code bit) lands on its own bit of the packed words, none
+    collide, and the place is the one the layout specification gives."""
     seen = set()
-    for col in range(kstep):
-        for cb in range(bits):
-            codes = np.zeros((16, kstep), dtype=np.uint8)
-            codes[5, col] = 1 << cb
-            packed = O.pack_codes(codes, bits)
-            nz = np.argwhere(packed != 0)
-            assert len(nz) == 1
-            jt, ks, plane, lane = nz[0]
-            word = int(packed[jt, ks, plane, lane])
-            assert word & (word - 1) == 0          # exactly one bit
-            assert lane % 16 == 5 and jt == 0 and ks == 0
-            assert lane // 16 == (col % 32) // 8   # the 8-column run decides the lane group
-            key = (plane, lane, word.bit_length() - 1)
-            assert key not in seen
-            seen.add(key)
-    assert len(seen) == kstep * bits
+    for row in (5, 21):
+        for col in range(128):
+            for cb in range(bits):
+                codes = np.zeros((32, 128), dtype=np.uint8)
+                codes[row, col] = 1 << cb
+                packed = O.pack_codes(codes, bits)
+                assert packed.shape == (2, 1, 128 * bits)        # rows are padded to 64
+                nz = np.argwhere(packed != 0)
+                assert len(nz) == 1 and nz[0][0] == 0 and nz[0][1] == 0
+                widx = int(nz[0][2])
+                word = int(packed[0, 0, widx])
+                assert word & (word - 1) == 0                    # exactly one bit
+                bit = word.bit_length() - 1
+                g, q, p = col // 32, (col % 32) // 8, col % 8
+                lane, rt = 16 * g + row % 16, row // 16
+                if bits == 1 or (bits == 3 and cb == 2):         # one word per (lane, rt), bit 4 p + q
+                    off = 256 if bits == 3 else 0
+                    assert (widx, bit) == (off + 2 * lane + rt, 4 * p + q)
+                else:                                            # two words per (lane, rt), 2-bit fields
+                    assert (widx, bit) == (4 * lane + 2 * rt + q // 2, 4 * p + 2 * (q % 2) + cb)
+                assert (widx, bit) not in seen
+                seen.add((widx, bit))
+    assert len(seen) == 2 * 128 * bits
+
+
+def test_packed_words_are_fp4_operands():
+    """The reason for the 4-bit fields: a 2-bit code u in the low half of a field is the fp4 (E2M1) bit
+    pattern of u / 2, a high bit in position 2 of a field is the pattern of 2.  E2M1: sign, two exponent
+    bits (bias 1), one mantissa bit; exponent 0 is subnormal (0 or 1/2)."""
+    def e2m1(n):
+        e, m = (n >> 1) & 3, n & 1
+        return (m * 0.5 if e == 0 else (1 + m * 0.5) * 2.0 ** (e - 1)) * (-1 if n & 8 else 1)
+    assert [e2m1(u) for u in range(4)] == [0.0, 0.5, 1.0, 1.5]
+    assert e2m1(0b0100) == 2.0
+    codes = _rng(9).integers(0, 8, size=(32, 128), dtype=np.uint8)
+    packed = O.pack_codes(codes, 3)[0, 0]
+    low, high = packed[:256].reshape(64, 2, 2), packed[256:].reshape(64, 2)
+    for lane in (0, 17, 63):
+        for rt in range(2):
+            row, g = 16 * rt + lane % 16, lane // 16
+            for q in range(4):
+                lo_reg = (int(low[lane, rt, q // 2]) >> (2 * (q % 2))) & 0x33333333
+                hi_reg = ((int(high[lane, rt]) << 2) >> q) & 0x44444444
+                for p in range(8):
+                    u = int(codes[row, 32 * g + 8 * q + p])
+                    assert e2m1((lo_reg >> (4 * p)) & 15) + e2m1((hi_reg >> (4 * p)) & 15) == u / 2
 
 
 def test_pack_padding_and_salient_are_zero_codes():
     codes = np.full((5, 70), 3, dtype=np.uint8)
     codes[:, [3, 17]] = O.SALIENT_MARK
     packed = O.pack_codes(codes, 2)
-    back = O.unpack_codes(packed, 2, 64, 512)
+    back = O.unpack_codes(packed, 2, 64, 128)
     assert back[:5, :70].sum() == 3 * 5 * 68
     assert back[5:].sum() == 0 and back[:, 70:].sum() == 0
     assert back[:5, 3].sum() == 0 and back[:5, 17].sum() == 0
@@ -77,7 +106,7 @@ def test_pack_padding_and_salient_are_zero_codes():
 def test_base_and_salient_tiling_roundtrip_and_slot_rule():
     w = _rng(3).integers(0, 65536, size=(70, 100), dtype=np.uint16)
     t = O.pack_base(w)
-    assert t.shape == (128 // 16, 512 // 32, 64, 8)
+    assert t.shape == (128 // 16, 128 // 32, 64, 8)
     assert np.array_equal(O.unpack_base(t, 70, 100), w)
     # slot rule stated independently: lane = 16 g + r holds W[16 jt + r, 32 kb + 8 g + e]
     for (j, i) in [(0, 0), (17, 45), (69, 99), (33, 8)]:
