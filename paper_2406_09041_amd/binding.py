@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libmes.so")
+LIB_PATH = os.environ.get("MES_LIBRARY") or os.path.join(_HERE, "libmes.so")   # MES_LIBRARY: another build of the same library
 
 MES_OK = 0
 GRID_SYM, GRID_EQ1 = 0, 1

@@ -34,6 +34,11 @@
 // a wave-uniform test on a per-lane token->slot table.
 #include "mes_internal.h"
 
+#ifdef MES_TRACE
+#include <cstdio>
+#include <cstdlib>
+#endif
+
 namespace mes {
 namespace {
 
@@ -48,8 +53,9 @@ constexpr int kStageVec = 2048;                 // 16-byte slots of activations 
 constexpr int kStageBytes = kStageVec * 16 + 256;   // + one block scale per token
 constexpr int kStageFp8 = 16384;                // byte offset of the fp8 pieces inside a stage
 constexpr int kStageScale = 32768;              // byte offset of the scales inside a stage
-constexpr int kMaxSlots = MES_MAX_EXPERTS;      // experts with tokens in one 64-token group
-constexpr int kSlotPad = 16;                    // slot tables are padded so that a full pass may overrun
+constexpr int kStageBlocks = 33;                // 1 KiB blocks the main kernel copies per chunk (the last one is partial)
+constexpr int kStageLds = kStageBlocks * 1024;  // LDS bytes of one stage
+constexpr int kMaxSlots = 16;                   // experts with tokens in one token group (the host cuts groups accordingly)
 constexpr int kMaxVisits = kMaxSlots + 3;       // (expert, 16-token tile) pairs in one group
 
 // Kernel arguments.  Per-expert arrays are indexed by slot.
@@ -61,7 +67,7 @@ struct LinearParams {
   u32x4* xs;        // workspace: salient activations per visit  [visit][k_pad/32][64 lanes]
   float* corr;      // workspace: per-token  z * (sum_all x - sum_salient x)  [64]
   float* partial;   // workspace: [nsplit][64 tokens][d_out_pad] fp32 (split columns only)
-  const char* codes[kMaxSlots + kSlotPad];
+  const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
   const char* sal[kMaxSlots];
   const int32_t* sidx[kMaxSlots];
@@ -70,7 +76,16 @@ struct LinearParams {
   uint8_t vis_slot[kMaxVisits + 1], vis_tt[kMaxVisits + 1];   // visits (slot, tile) in tile-major order
   int d_in, d_out, d_out_pad, n_kb, n_chunks, n_jp, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
   float z;
+#ifdef MES_TRACE
+  unsigned long long* trace;   // development builds only: [call][workgroup][16] timestamps
+#endif
 };
+
+#ifdef MES_TRACE
+#define MES_STAMP(i) do { if (threadIdx.x == 0) p.trace[((size_t)(blockIdx.y * gridDim.x + blockIdx.x)) * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define MES_STAMP(i) do { } while (0)
+#endif
 
 __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -350,20 +365,134 @@ __device__ __forceinline__ void compute_sal(const LinearParams& p, int pair, con
   }
 }
 
-// Waits for this wavefront's LDS writes, then for every wavefront of the workgroup.  (A plain barrier: the
-// global loads a wavefront has in flight -- next chunk's weights -- are not waited for.)
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
+
+// Copies one chunk's stage from memory straight into LDS (no registers in between): wavefront `wave` of NW
+// copies the 1 KiB blocks wave, wave + NW, ... (33 blocks; block numbers past the last are clamped, which
+// rewrites the last block with the same bytes).  The number of copy instructions per wavefront is a
+// compile-time constant, so the wait below can name exactly how many younger loads may still be in flight.
+template <int NW>
+__device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, int wave, int lane) {
+  constexpr int KD = (kStageBlocks + NW - 1) / NW;
+#pragma unroll
+  for (int i = 0; i < KD; ++i) {
+    int blk = wave + NW * i;
+    blk = blk < kStageBlocks ? blk : kStageBlocks - 1;
+    __builtin_amdgcn_global_load_lds((global_void*)(src + blk * 1024 + lane * 16), (lds_void*)(dst_lds + blk * 1024), 16, 0, 0);
+  }
+  asm volatile("" ::: "memory");   // later loads stay later: stage_barrier counts them
+}
+
+// vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
+
+// Waits until at most `younger` of this wavefront's loads are in flight (loads complete in order, so the
+// stage copy issued before them has landed), for its LDS accesses, and then for the whole workgroup.
+// Deliberately not __syncthreads(): that would also wait for the weight loads of the next chunk.
+template <int YOUNGER>
+__device__ __forceinline__ void stage_barrier() {
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm(YOUNGER) & ~0x0f00);   // vmcnt(YOUNGER) lgkmcnt(0)
+  asm volatile("s_barrier" ::: "memory");
 }
 
 template <int BITS, int TT, int NA, int NW>
-__global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) {
+struct Stream {
   using C = Codec<BITS>;
-  constexpr int NT = 64 * NW;
-  constexpr int XV = kStageVec / NT;        // 16-byte activation slots each thread copies per chunk
-  constexpr int D = 4;                      // code-word loads in flight per wavefront (register ring); divides NA
+  static constexpr int kLoadsPerSlot = BITS == 3 ? 2 : 1;
+  static constexpr int kWeightLoads = 8 + NA * kLoadsPerSlot;   // per wavefront and chunk
+  static constexpr int kSlotsPerBase = NA / 4;                  // slots between two 32-column base blocks
+
+  const LinearParams& p;
+  int lane, n, jp;
+  const char* base_ptr;
+  size_t base_rt_stride;
+  uint32_t slot_tok[TT];
+  u32x4 base[2][4];
+  CodeRegs<BITS> code[NA];
+  f32x4 acc_base[2][TT], acc_raw[2][TT];
+
+  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jp_) : p(p_), lane(lane_), n(lane_ & 15), jp(jp_) {
+    base_ptr = p.w_base + (size_t)(2 * jp) * p.n_kb * 1024 + lane * 16;
+    base_rt_stride = (size_t)p.n_kb * 1024;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) slot_tok[tt] = p.tok_slot[16 * tt + n];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) { acc_base[rt][tt] = f32x4{0, 0, 0, 0}; acc_raw[rt][tt] = f32x4{0, 0, 0, 0}; }
+  }
+
+  __device__ __forceinline__ void load_base(int c, int kb) {
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) base[rt][kb] = *reinterpret_cast<const u32x4*>(base_ptr + rt * base_rt_stride + (size_t)(4 * c + kb) * 1024);
+  }
+
+  __device__ __forceinline__ void load_all(int c) {
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) load_base(c, kb);
+#pragma unroll
+    for (int a = 0; a < NA; ++a) load_codes<BITS>(p.codes[a], jp, c, p.n_chunks, lane, code[a]);
+  }
+
+  // One chunk: its activations are in `cur`; the next chunk's are copied into `nxt` meanwhile.  Every weight
+  // register is reloaded with the next chunk's data right after its last use, so all of a wavefront's
+  // weight bytes for one chunk are in flight or waiting in registers at any time.
+  __device__ __forceinline__ void chunk(int c, int cn, const char* cur, char* nxt, int wave) {
+    stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
+    int scale_tok[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) scale_tok[tt] = *reinterpret_cast<const int*>(cur + kStageScale + (16 * tt + n) * 4);
+    int bcur = -1;
+    v8i bhi = {0, 0, 0, 0, 0, 0, 0, 0}, blo = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+      if (a % kSlotsPerBase == 0) {   // a 32-column block of the base product between groups of slots
+        const int kb = a / kSlotsPerBase;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+          const u32x4 xb = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt) acc_base[rt][tt] = mfma_bf16(base[rt][kb], xb, acc_base[rt][tt]);
+        }
+        load_base(cn, kb);
+      }
+      u32x4 dq[2], dqh[2];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        dq[rt] = dequant_lo<BITS>(code[a], rt);
+        if constexpr (BITS == 3) dqh[rt] = dequant_hi(code[a], rt);
+      }
+      load_codes<BITS>(p.codes[a], jp, cn, p.n_chunks, lane, code[a]);
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        const bool mine = slot_tok[tt] == (uint32_t)a;
+        if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+          if (bcur != tt) {
+            bhi = lds_fp8(cur, tt, 0, lane);
+            blo = lds_fp8(cur, tt, 1, lane);
+            bcur = tt;
+          }
+          const int sc = mine ? scale_tok[tt] : 0;
+          acc_raw[0][tt] = mfma_fp4_fp8(dq[0], bhi, acc_raw[0][tt], sc);
+          acc_raw[1][tt] = mfma_fp4_fp8(dq[1], bhi, acc_raw[1][tt], sc);
+          acc_raw[0][tt] = mfma_fp4_fp8(dq[0], blo, acc_raw[0][tt], sc);
+          acc_raw[1][tt] = mfma_fp4_fp8(dq[1], blo, acc_raw[1][tt], sc);
+          if constexpr (BITS == 3) {
+            acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], bhi, acc_raw[0][tt], sc);
+            acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], bhi, acc_raw[1][tt], sc);
+            acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], blo, acc_raw[0][tt], sc);
+            acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], blo, acc_raw[1][tt], sc);
+          }
+        }
+      }
+    }
+    stage_barrier<kWeightLoads>();
+  }
+};
+
+template <int BITS, int TT, int NA, int NW>
+__global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   // The wavefront index is the same in all 64 lanes; saying so keeps every value derived from it in scalar
   // registers and every branch on them a scalar branch.  MFMA ignores the EXEC mask, so an MFMA must never
@@ -376,130 +505,34 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   jp = live ? jp : p.n_jp - 1;
   const int c_begin = (int)((long)sp * p.n_chunks / p.nsplit);
   const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
+  MES_STAMP(0);
 
-  __shared__ __attribute__((aligned(16))) char smem[2][kStageBytes];
+  // two stages, as two arrays: the compiler then knows that a copy into one never touches what is read from the other
+  __shared__ __attribute__((aligned(16))) char stage0[kStageLds];
+  __shared__ __attribute__((aligned(16))) char stage1[kStageLds];
 
-  uint32_t slot_tok[TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) slot_tok[tt] = p.tok_slot[16 * tt + n];
+  Stream<BITS, TT, NA, NW> ws(p, lane, jp);
+  f32x4 (&acc_base)[2][TT] = ws.acc_base;
+  f32x4 (&acc_raw)[2][TT] = ws.acc_raw;
+  const uint32_t (&slot_tok)[TT] = ws.slot_tok;
 
-  f32x4 acc_base[2][TT], acc_raw[2][TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt) { acc_base[rt][tt] = f32x4{0, 0, 0, 0}; acc_raw[rt][tt] = f32x4{0, 0, 0, 0}; }
-
-  const char* base_ptr = p.w_base + (size_t)(2 * jp) * p.n_kb * 1024 + lane * 16;   // row tile 2 jp, block 0
-  const size_t base_rt_stride = (size_t)p.n_kb * 1024;
-
-  // Slots are processed NA at a time; with more than NA active experts in the group the column range is
-  // streamed once per pass (the base product only in the first).
-  for (int a0 = 0; a0 < p.n_act && c_begin < c_end; a0 += NA) {
-    const bool do_base = a0 == 0;
-    u32x4 base[2][4];
-    CodeRegs<BITS> ring[D];
-    u32x4 xst[XV];
-    u32x4 xsc = {0, 0, 0, 0};
-
-    // prologue: first chunk's activations into stage 0, its weights into registers
-    {
-      const char* src = p.xt + (size_t)c_begin * kStageBytes;
-#pragma unroll
-      for (int i = 0; i < XV; ++i) xst[i] = ld128(src + (size_t)i * NT * 16, (uint32_t)tid * 16u);
-      if (tid < 16) xsc = ld128(src + kStageScale, (uint32_t)tid * 16u);
-      if (do_base)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-          for (int kb = 0; kb < 4; ++kb) base[rt][kb] = *reinterpret_cast<const u32x4*>(base_ptr + rt * base_rt_stride + (size_t)(4 * c_begin + kb) * 1024);
-#pragma unroll
-      for (int a = 0; a < D; ++a) load_codes<BITS>(p.codes[a0 + a], jp, c_begin, p.n_chunks, lane, ring[a]);
-#pragma unroll
-      for (int i = 0; i < XV; ++i) *reinterpret_cast<u32x4*>(&smem[0][(i * NT + tid) * 16]) = xst[i];
-      if (tid < 16) *reinterpret_cast<u32x4*>(&smem[0][kStageScale + tid * 16]) = xsc;
-      lds_barrier();
-    }
-
-    for (int c = c_begin; c < c_end; ++c) {
-      const char* stage = smem[(c - c_begin) & 1];
-      char* stage_next = smem[((c - c_begin) & 1) ^ 1];
-      const int cn = c + 1 < c_end ? c + 1 : c;
-      // next chunk's activations: global -> registers now, registers -> LDS at the end of this chunk
-      {
-        const char* src = p.xt + (size_t)cn * kStageBytes;
-#pragma unroll
-        for (int i = 0; i < XV; ++i) xst[i] = ld128(src + (size_t)i * NT * 16, (uint32_t)tid * 16u);
-        if (tid < 16) xsc = ld128(src + kStageScale, (uint32_t)tid * 16u);
-      }
-      int scale_tok[TT];
-#pragma unroll
-      for (int tt = 0; tt < TT; ++tt) scale_tok[tt] = *reinterpret_cast<const int*>(stage + kStageScale + (16 * tt + n) * 4);
-
-      if (do_base) {
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-          for (int tt = 0; tt < TT; ++tt) {
-            const u32x4 xb = lds128(stage, (kb * 4 + tt) * 1024 + lane * 16);
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt) acc_base[rt][tt] = mfma_bf16(base[rt][kb], xb, acc_base[rt][tt]);
-          }
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-          for (int kb = 0; kb < 4; ++kb) base[rt][kb] = *reinterpret_cast<const u32x4*>(base_ptr + rt * base_rt_stride + (size_t)(4 * cn + kb) * 1024);
-      }
-
-      int bcur = -1;
-      v8i bhi = {0, 0, 0, 0, 0, 0, 0, 0}, blo = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-      for (int a = 0; a < NA; ++a) {
-        CodeRegs<BITS>& cr = ring[a % D];
-        u32x4 dq[2], dqh[2];
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-          dq[rt] = dequant_lo<BITS>(cr, rt);
-          if constexpr (BITS == 3) dqh[rt] = dequant_hi(cr, rt);
-        }
-        // refill the ring entry: slot a + D of this chunk, or of the next chunk once the slots wrap
-        {
-          const int na = a + D < NA ? a + D : a + D - NA;
-          const int cc = a + D < NA ? c : cn;
-          load_codes<BITS>(p.codes[a0 + na], jp, cc, p.n_chunks, lane, cr);
-        }
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          const bool mine = slot_tok[tt] == (uint32_t)(a0 + a);
-          if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-            if (bcur != tt) {
-              bhi = lds_fp8(stage, tt, 0, lane);
-              blo = lds_fp8(stage, tt, 1, lane);
-              bcur = tt;
-            }
-            const int sc = mine ? scale_tok[tt] : 0;
-            acc_raw[0][tt] = mfma_fp4_fp8(dq[0], bhi, acc_raw[0][tt], sc);
-            acc_raw[1][tt] = mfma_fp4_fp8(dq[1], bhi, acc_raw[1][tt], sc);
-            acc_raw[0][tt] = mfma_fp4_fp8(dq[0], blo, acc_raw[0][tt], sc);
-            acc_raw[1][tt] = mfma_fp4_fp8(dq[1], blo, acc_raw[1][tt], sc);
-            if constexpr (BITS == 3) {
-              acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], bhi, acc_raw[0][tt], sc);
-              acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], bhi, acc_raw[1][tt], sc);
-              acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], blo, acc_raw[0][tt], sc);
-              acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], blo, acc_raw[1][tt], sc);
-            }
-          }
-        }
-      }
-
-#pragma unroll
-      for (int i = 0; i < XV; ++i) *reinterpret_cast<u32x4*>(&stage_next[(i * NT + tid) * 16]) = xst[i];
-      if (tid < 16) *reinterpret_cast<u32x4*>(&stage_next[kStageScale + tid * 16]) = xsc;
-      lds_barrier();
-    }
+  // prologue: first chunk's activations into stage 0, its weights into registers
+  stage_copy<NW>(p.xt + (size_t)c_begin * kStageBytes, stage0, wave, lane);
+  ws.load_all(c_begin);
+  stage_barrier<Stream<BITS, TT, NA, NW>::kWeightLoads>();
+  MES_STAMP(1);
+  for (int c = c_begin; c < c_end; c += 2) {
+    ws.chunk(c, c + 1 < c_end ? c + 1 : c, stage0, stage1, wave);
+    if (c - c_begin < 10) MES_STAMP(2 + c - c_begin);
+    if (c + 1 >= c_end) break;
+    ws.chunk(c + 1, c + 2 < c_end ? c + 2 : c + 1, stage1, stage0, wave);
+    if (c + 1 - c_begin < 10) MES_STAMP(3 + c - c_begin);
   }
 
+  MES_STAMP(12);
   // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits; the
   // wavefront prefetches its next pair while it multiplies the current one
+  MES_STAMP(12);
   if (p.k > 0) {
     const int n_pairs = p.n_vis * p.n_sb;
     const int stride = p.nsplit;
@@ -523,6 +556,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   }
 
   // epilogue: remove the zero point, apply the expert's step
+  MES_STAMP(13);
   if (!live) return;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
@@ -550,6 +584,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
       }
     }
   }
+  MES_STAMP(14);
 }
 
 // Split columns only: y = sum over splits (in split order) of the fp32 partial tiles, rounded to bf16.
@@ -567,26 +602,41 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const LinearParams p, int
   *reinterpret_cast<uint2*>(p.y + (size_t)(p.t0 + tl) * p.d_out + j) = pk;
 }
 
-constexpr int kWaves = 4;           // wavefronts per workgroup; each owns 32 output channels
+constexpr int kMaxPassSlots = 16;   // active experts one launch handles (its code words live in registers)
 
 struct Plan {
+  int nw;      // wavefronts per workgroup; each owns 32 output channels
   int nsplit;  // workgroups that share one row group's columns
 };
 
-// Pure function of the layer shape (not of bits or T), so the workspace size is known up front.  Two
-// workgroups fit a compute unit; columns are split over workgroups until there are about two per unit,
-// keeping at least four chunks per workgroup.
+// Pure function of the layer shape (not of bits or T), so the workspace size is known up front.
+// One workgroup runs per compute unit (256 of them): the shape's row tile pairs are grouped NW to a
+// workgroup and the chunks split over `nsplit` workgroups so that the grid comes as close as possible to
+// a whole number of rounds of 256, with at least four chunks per workgroup and few splits (every split
+// writes and re-reads a partial output tile).
 Plan plan_for(int d_in, int d_out) {
-  const int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
-  const int n_chunks = pi / kChunk;
-  const int row_groups = (po / 32 + kWaves - 1) / kWaves;
-  int ns = (512 + row_groups - 1) / row_groups;
-  const int max_split = n_chunks / 4 > 0 ? n_chunks / 4 : 1;
-  if (ns > max_split) ns = max_split;
-  if (ns < 1) ns = 1;
-  Plan pl;
-  pl.nsplit = ns;
-  return pl;
+  const int n_jp = ceil_to(d_out, kRowPad) / 32, n_chunks = ceil_to(d_in, kColPad) / kChunk;
+#ifdef MES_TRACE
+  if (const char* ov = getenv("MES_PLAN")) { Plan o{4, 1}; if (sscanf(ov, "%d,%d", &o.nw, &o.nsplit) == 2) return o; }
+#endif
+  static const int kNw[] = {4, 2, 1};
+  Plan best{4, 1};
+  double best_cost = 1e30;
+  for (int nw : kNw) {
+    const int rgs = (n_jp + nw - 1) / nw;
+    for (int ns = 1; ns <= 32 && ns * 4 <= (n_chunks < 4 ? 4 : n_chunks); ++ns) {
+      const long wgs = (long)rgs * ns;
+      const long rounds = (wgs + 255) / 256;
+      const int chunks_wg = (n_chunks + ns - 1) / ns;
+      // time ~ rounds x (chunks per workgroup + fixed start-up/finish cost in chunk units), at a per-unit rate
+      // that improves with the number of wavefronts of a unit sharing one staged activation chunk
+      const double per_chunk = nw * 1.0 + 1.5;                 // weight bytes + activation copy, relative
+      double cost = (double)rounds * (chunks_wg * per_chunk + 6.0 * (nw < 4 ? 4 : nw) / 4.0);
+      cost += ns > 1 ? 0.35 * ns : 0.0;                        // partial tiles: written, then read by the reduction
+      if (cost < best_cost) { best_cost = cost; best = Plan{nw, ns}; }
+    }
+  }
+  return best;
 }
 
 struct WorkspaceLayout {
@@ -598,7 +648,7 @@ WorkspaceLayout workspace_layout(int d_in, int d_out) {
   const int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
   WorkspaceLayout w;
   size_t off = 0;
-  w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes;
+  w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes + 1024;   // the copy of the last stage's partial block reads a full KiB
   w.xs = off;      off += (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
   w.corr = off;    off += 256;
   w.partial = off; off += pl.nsplit > 1 ? (size_t)pl.nsplit * kTokGroup * po * sizeof(float) : 0;
@@ -607,28 +657,36 @@ WorkspaceLayout workspace_layout(int d_in, int d_out) {
 }
 
 template <int BITS, int TT, int NA>
-hipError_t launch_main(const LinearParams& p, dim3 grid, hipStream_t s) {
-  k_delta_linear<BITS, TT, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p);
+hipError_t launch_nw(const LinearParams& p, int nw, dim3 grid, hipStream_t s) {
+  switch (nw) {
+    case 1: k_delta_linear<BITS, TT, NA, 1><<<grid, 64, 0, s>>>(p); break;
+    case 2: k_delta_linear<BITS, TT, NA, 2><<<grid, 128, 0, s>>>(p); break;
+    default: k_delta_linear<BITS, TT, NA, 4><<<grid, 256, 0, s>>>(p); break;
+  }
   return hipGetLastError();
 }
 
 template <int BITS, int NA>
-hipError_t launch_tt(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
+hipError_t launch_tt(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
   switch (tt) {
-    case 1: return launch_main<BITS, 1, NA>(p, grid, s);
-    case 2: return launch_main<BITS, 2, NA>(p, grid, s);
-    default: return launch_main<BITS, 4, NA>(p, grid, s);
+    case 1: return launch_nw<BITS, 1, NA>(p, nw, grid, s);
+    case 2: return launch_nw<BITS, 2, NA>(p, nw, grid, s);
+    default: return launch_nw<BITS, 4, NA>(p, nw, grid, s);
   }
 }
 
 template <int BITS>
-hipError_t launch_na(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
-  if (p.n_act <= 4) return launch_tt<BITS, 4>(p, tt, grid, s);
-  if (p.n_act <= 8) return launch_tt<BITS, 8>(p, tt, grid, s);
-  return launch_tt<BITS, 16>(p, tt, grid, s);
+hipError_t launch_na(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
+  if (p.n_act <= 4) return launch_tt<BITS, 4>(p, tt, nw, grid, s);
+  return launch_tt<BITS, kMaxPassSlots>(p, tt, nw, grid, s);
 }
 
 }  // namespace
+
+#ifdef MES_TRACE
+unsigned long long* g_trace = nullptr;
+int g_call = 0;
+#endif
 
 size_t linear_workspace_bytes(int d_in, int d_out, int max_tokens) {
   (void)max_tokens;  // one 64-token group is in flight at a time
@@ -641,6 +699,11 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   const WorkspaceLayout wl = workspace_layout(d0.d_in, d0.d_out);
   char* ws = reinterpret_cast<char*>(c.ws);
   LinearParams p;
+#ifdef MES_TRACE
+  if (!g_trace) { if (hipMalloc(&g_trace, (size_t)64 << 20) != hipSuccess) return hipErrorOutOfMemory; (void)hipMemset(g_trace, 0, (size_t)64 << 20); }
+  p.trace = g_trace + (size_t)(g_call % 64) * (1 << 17);
+  ++g_call;
+#endif
   p.w_base = reinterpret_cast<const char*>(c.w_base);
   p.x = reinterpret_cast<const uint16_t*>(c.x);
   p.y = reinterpret_cast<uint16_t*>(c.y);
@@ -661,15 +724,25 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.nsplit = pl.nsplit;
   p.bits = d0.bits;
   p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
-  const dim3 grid((p.n_jp + kWaves - 1) / kWaves, pl.nsplit);
-  for (int t0 = 0; t0 < c.T; t0 += kTokGroup) {
+  const dim3 grid((p.n_jp + pl.nw - 1) / pl.nw, pl.nsplit);
+  // Token groups: up to 64 consecutive tokens that belong to at most kMaxPassSlots experts.
+  int e_cur = 0;   // first expert that may own token t0
+  for (int t0 = 0; t0 < c.T;) {
+    while (c.seg[e_cur + 1] <= t0) ++e_cur;
+    int nt = c.T - t0 < kTokGroup ? c.T - t0 : kTokGroup;
+    {   // cut the group where the (kMaxPassSlots + 1)-th active expert would start
+      int act = 0;
+      for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
+        if (c.seg[e + 1] <= c.seg[e]) continue;
+        if (++act > kMaxPassSlots) { nt = c.seg[e] - t0; break; }
+      }
+    }
     p.t0 = t0;
-    const int nt = c.T - t0 < kTokGroup ? c.T - t0 : kTokGroup;
-    const int tt = (nt + 15) / 16;
+    const int tt = nt <= 16 ? 1 : nt <= 32 ? 2 : 4;
     // active slots: the experts that own tokens of this group, in expert order
     int na = 0;
     for (int tl = 0; tl < kTokGroup; ++tl) p.tok_slot[tl] = 0xff;
-    for (int e = 0; e < c.n_experts; ++e) {
+    for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
       const int lo = (c.seg[e] > t0 ? c.seg[e] : t0) - t0;
       const int hi = (c.seg[e + 1] < t0 + nt ? c.seg[e + 1] : t0 + nt) - t0;
       if (hi <= lo) continue;
@@ -682,11 +755,10 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       for (int tl = lo; tl < hi; ++tl) p.tok_slot[tl] = (uint8_t)na;
       ++na;
     }
-    for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional prefetches stay valid
-      p.step[a] = p.step[0]; p.sal[a] = p.sal[0]; p.sidx[a] = p.sidx[0];
+    for (int a = na; a < kMaxPassSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
+      p.codes[a] = p.codes[0]; p.step[a] = p.step[0]; p.sal[a] = p.sal[0]; p.sidx[a] = p.sidx[0];
       p.lo[a] = 0; p.hi[a] = 0;
     }
-    for (int a = na; a < kMaxSlots + kSlotPad; ++a) p.codes[a] = p.codes[0];
     // visits, tile-major: for every 16-token tile the slots that own tokens in it
     int nv = 0;
     for (int t = 0; t < 4; ++t)
@@ -701,13 +773,14 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     for (int v = nv; v <= kMaxVisits; ++v) { p.vis_slot[v] = 0; p.vis_tt[v] = 0; }
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
+    p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
     k_prepare<<<p.n_chunks + p.n_vis + kTokGroup, 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     switch (d0.bits) {
-      case 1: e = launch_na<1>(p, tt, grid, s); break;
-      case 2: e = launch_na<2>(p, tt, grid, s); break;
-      default: e = launch_na<3>(p, tt, grid, s); break;
+      case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
+      case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
+      default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
     }
     if (e != hipSuccess) return e;
     if (pl.nsplit > 1) {
@@ -715,8 +788,18 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       k_reduce_splits<<<(total + 255) / 256, 256, 0, s>>>(p, nt);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
+    t0 += nt;
   }
   return hipSuccess;
 }
 
 }  // namespace mes
+
+#ifdef MES_TRACE
+// Development builds only: copy call slot `slot` (of the last 64 calls) of the timestamp trace to the host.
+extern "C" int mes_debug_trace(int slot, unsigned long long* out, size_t n) {
+  if (!mes::g_trace) return 1;
+  return (int)hipMemcpy(out, mes::g_trace + (size_t)(slot % 64) * (1 << 17), n * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+}
+extern "C" int mes_debug_calls(void) { return mes::g_call; }
+#endif
