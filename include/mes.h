@@ -29,21 +29,21 @@
  * Storage layouts (tile-major, so that one 64-lane wavefront reads contiguous
  * memory and holds a matrix-core operand without any shuffle).  A "lane slot" is
  * lane = 16 g + r: r = row inside a 16-row tile, g = one of four column groups.
- *  - base:    uint16 (bf16 bits) [d_out_pad/16][d_in_pad/32][64 lanes][8];
- *             slot (jt, kb, lane, e) holds W[16 jt + r][32 kb + 8 g + e].
+ *  - base:    uint16 (bf16 bits) [d_in_pad/128][d_out_pad/16][4][64 lanes][8], chunk-major:
+ *             all row tiles of one 128-column chunk are contiguous;
+ *             slot (c, jt, kb, lane, e) holds W[16 jt + r][128 c + 32 kb + 8 g + e].
  *  - salient: uint16 (fp16 bits) [d_out_pad/16][k_pad/32][64][8];
  *             slot (jt, sb, lane, e) holds fp16(Delta[16 jt + r][S[32 sb + 8 g + e]]).
- *  - codes:   blocks of 32 rows x 128 columns, [d_out_pad/32][d_in_pad/128], 512 b
- *             bytes each.  Inside block (jp, c) the lane 16 g + r owns, for each of its
- *             two row tiles rt (row = 32 jp + 16 rt + r), the 32 columns
- *             128 c + 32 g + e, e = 8 q + p (q < 4, p < 8).  Codes sit in 4-bit fields
- *             (field p of a 32-bit word = bits [4 p, 4 p + 4)) so that one AND turns a
- *             word into eight fp4 (E2M1) matrix-core inputs:
- *               b = 1: uint32 [64 lanes][2 rt]; code of element (q, p) at bit 4 p + q.
- *               b = 2: uint32 [64 lanes][2 rt][2 w]; code of element (q, p) in word
- *                      w = q / 2 at bits [4 p + 2 (q % 2), + 2).
- *               b = 3: the b = 2 block holding the low two code bits (1024 bytes),
- *                      followed by a b = 1 block holding the high code bit (512 bytes).
+ *  - codes:   blocks of 16 rows x 128 columns, [d_in_pad/128][d_out_pad/16] (chunk-major
+ *             like the base), 256 b bytes each.  Inside block (c, jt) the lane 16 g + r owns
+ *             row 16 jt + r and the 32 columns 128 c + 32 g + e, e = 8 q + p (q < 4, p < 8).
+ *             Codes sit in 4-bit fields (field p of a 32-bit word = bits [4 p, 4 p + 4)) so
+ *             that one AND turns a word into eight fp4 (E2M1) matrix-core inputs:
+ *               b = 1: uint32 [64 lanes]; code of element (q, p) at bit 4 p + q.
+ *               b = 2: uint32 [64 lanes][2 w]; code of element (q, p) in word w = q / 2 at
+ *                      bits [4 p + 2 (q % 2), + 2).
+ *               b = 3: the b = 2 block holding the low two code bits (512 bytes), followed
+ *                      by a b = 1 block holding the high code bit (256 bytes).
  *             Codes of salient columns, padding columns and padding rows are 0.
  *    The code u is unsigned; the weight it stands for is (u - z) * step[row] with
  *    z = 2^(b-1) - 1/2 (MES_GRID_SYM) or 2^(b-1) (MES_GRID_EQ1, Eq. 1's levels).
@@ -79,7 +79,7 @@ enum { MES_GRID_SYM = 0, MES_GRID_EQ1 = 1 };
 enum { MES_STEP_GIVEN = 0, MES_STEP_MAXABS = 1, MES_STEP_MEANABS = 2 };
 
 #define MES_MAX_EXPERTS 64
-#define MES_LAYOUT_VERSION 2
+#define MES_LAYOUT_VERSION 3
 
 /* One expert's compressed delta for one linear layer (all pointers DEVICE, caller-owned). */
 typedef struct {

@@ -244,16 +244,23 @@ def _untile_16x32(t: np.ndarray) -> np.ndarray:
 
 
 def pack_base(w_bits: np.ndarray) -> np.ndarray:
-    """bf16 bit patterns [d_out, d_in] uint16 -> tiled uint16 [d_out_pad/16, d_in_pad/32, 64, 8], zero padded."""
+    """bf16 bit patterns [d_out, d_in] uint16 -> tiled uint16 [d_in_pad/128, d_out_pad/16, 4, 64, 8], zero padded.
+
+    Chunk-major: all row tiles of one 128-column chunk are contiguous; slot (c, jt, kb, lane, e) with
+    lane = 16 g + r holds W[16 jt + r, 128 c + 32 kb + 8 g + e]."""
     d_out, d_in = w_bits.shape
     po, pi, _ = padded_dims(d_out, d_in)
     a = np.zeros((po, pi), dtype=np.uint16)
     a[:d_out, :d_in] = w_bits
-    return _tile_16x32(a)
+    t = _tile_16x32(a)                                   # jt, kb_all, lane, e
+    t = t.reshape(po // 16, pi // 128, 4, 64, 8)         # jt, c, kb, lane, e
+    return np.ascontiguousarray(t.transpose(1, 0, 2, 3, 4))
 
 
 def unpack_base(t: np.ndarray, d_out: int, d_in: int) -> np.ndarray:
-    return _untile_16x32(t)[:d_out, :d_in]
+    nc, njt = t.shape[0], t.shape[1]
+    u = np.ascontiguousarray(t.transpose(1, 0, 2, 3, 4)).reshape(njt, nc * 4, 64, 8)
+    return _untile_16x32(u)[:d_out, :d_in]
 
 
 def pack_salient(salient16: np.ndarray) -> np.ndarray:
@@ -292,12 +299,13 @@ def _unnibble_words(words: np.ndarray, width: int) -> np.ndarray:
 
 
 def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
-    """Logical codes uint8 [d_out, d_in] (0xFF = salient) -> uint32 [d_out_pad/32, d_in_pad/128, 128 * bits].
+    """Logical codes uint8 [d_out, d_in] (0xFF = salient) -> uint32 [d_in_pad/128, d_out_pad/16, 64 * bits].
 
-    Blocks of 32 rows x 128 columns.  Lane 16 g + r owns, for each of its two row tiles rt, the 32 columns
-    32 g + 8 q + p.  b = 1: words [lane][rt], code at bit 4 p + q.  b = 2: words [lane][rt][w], code of (q, p)
-    in word q // 2 at bits 4 p + 2 (q % 2).  b = 3: the b = 2 block of the low two bits, then the b = 1 block
-    of the high bit.  Salient columns, padding columns and padding rows store code 0.
+    Blocks of 16 rows x 128 columns, chunk-major (all row tiles of one 128-column chunk are contiguous).
+    Lane 16 g + r owns row 16 jt + r and the 32 columns 128 c + 32 g + 8 q + p.  b = 1: one word per lane,
+    code at bit 4 p + q.  b = 2: words [lane][w], code of (q, p) in word q // 2 at bits 4 p + 2 (q % 2).
+    b = 3: the b = 2 block of the low two bits, then the b = 1 block of the high bit.  Salient columns,
+    padding columns and padding rows store code 0.
     """
     d_out, d_in = codes.shape
     po, pi, _ = padded_dims(d_out, d_in)
@@ -305,29 +313,29 @@ def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
     c = codes.astype(np.uint32)
     c[codes == SALIENT_MARK] = 0
     u[:d_out, :d_in] = c
-    v = u.reshape(po // 32, 2, 16, pi // 128, 4, 4, 8)          # jp, rt, r, c, g, q, p
-    v = v.transpose(0, 3, 4, 2, 1, 5, 6)                         # jp, c, g, r, rt, q, p
-    v = v.reshape(po // 32, pi // 128, 64, 2, 4, 8)              # jp, c, lane, rt, q, p
+    v = u.reshape(po // 16, 16, pi // 128, 4, 4, 8)              # jt, r, c, g, q, p
+    v = v.transpose(2, 0, 3, 1, 4, 5)                            # c, jt, g, r, q, p
+    v = v.reshape(pi // 128, po // 16, 64, 4, 8)                 # c, jt, lane, q, p
     if bits == 1:
-        return _nibble_words(v, 1).reshape(po // 32, pi // 128, 128)
-    low = _nibble_words(v & np.uint32(3), 2).reshape(po // 32, pi // 128, 256)
+        return _nibble_words(v, 1).reshape(pi // 128, po // 16, 64)
+    low = _nibble_words(v & np.uint32(3), 2).reshape(pi // 128, po // 16, 128)
     if bits == 2:
         return low
-    high = _nibble_words(v >> np.uint32(2), 1).reshape(po // 32, pi // 128, 128)
+    high = _nibble_words(v >> np.uint32(2), 1).reshape(pi // 128, po // 16, 64)
     return np.concatenate([low, high], axis=2)
 
 
 def unpack_codes(packed: np.ndarray, bits: int, d_out: int, d_in: int) -> np.ndarray:
     """Inverse of pack_codes (salient columns come back as code 0)."""
-    njp, nc = packed.shape[0], packed.shape[1]
+    nc, njt = packed.shape[0], packed.shape[1]
     if bits == 1:
-        v = _unnibble_words(packed.reshape(njp, nc, 64, 2, 1), 1)
+        v = _unnibble_words(packed.reshape(nc, njt, 64, 1), 1)
     else:
-        v = _unnibble_words(packed[:, :, :256].reshape(njp, nc, 64, 2, 2), 2)
+        v = _unnibble_words(packed[:, :, :128].reshape(nc, njt, 64, 2), 2)
         if bits == 3:
-            v = v | (_unnibble_words(packed[:, :, 256:].reshape(njp, nc, 64, 2, 1), 1) << np.uint32(2))
-    v = v.reshape(njp, nc, 4, 16, 2, 4, 8).transpose(0, 4, 3, 1, 2, 5, 6)   # jp, rt, r, c, g, q, p
-    return np.ascontiguousarray(v).reshape(njp * 32, nc * 128)[:d_out, :d_in].astype(np.uint8)
+            v = v | (_unnibble_words(packed[:, :, 128:].reshape(nc, njt, 64, 1), 1) << np.uint32(2))
+    v = v.reshape(nc, njt, 4, 16, 4, 8).transpose(1, 3, 0, 2, 4, 5)   # jt, r, c, g, q, p
+    return np.ascontiguousarray(v).reshape(njt * 16, nc * 128)[:d_out, :d_in].astype(np.uint8)
 
 
 def codes_bytes(d_in: int, d_out: int, bits: int) -> int:

@@ -3,10 +3,11 @@
 // for groups of up to 64 tokens.  Per group: one small preparation launch, the main streaming launch
 // and, only when the columns had to be split over workgroups, a small reduction launch.
 //
-// Main kernel.  A workgroup owns 32 * NW output channels (one pair of 16-row tiles per wavefront) and a
-// range of 128-column chunks.  The activations of a chunk are shared by all wavefronts through LDS
-// (double buffered, copied from the preparation kernel's output one chunk ahead); every weight byte is
-// read once, straight from memory into the registers of the one wavefront that needs it, one chunk ahead.
+// Main kernel.  A workgroup of eight wavefronts (two per SIMD: while one waits for memory or for the
+// matrix core the other issues) owns 128 output channels, one 16-row tile per wavefront, and a range of
+// 128-column chunks.  The activations of a chunk are shared by all wavefronts through LDS (double
+// buffered, copied memory -> LDS one chunk ahead); every weight byte is read once, by the one wavefront
+// that needs it, at least one chunk ahead.
 //
 // Three products accumulate per wavefront, all on the matrix cores, weights as the A operand (16 output
 // channels), tokens as the B operand (16 tokens), so a result tile is [channel][token]:
@@ -21,19 +22,23 @@
 //            2^-17 of that largest value).  The instruction's per-lane block scale (a power of two applied
 //            to a token's products) carries 2^(s+1) for tokens of the expert being multiplied and 2^-127
 //            for every other token of the tile -- that is how several experts share a 16-token tile.
-//   salient  each fp16 value is split exactly into two bf16 values (11 significant bits into 2 x 8), so
-//            two bf16 MFMAs reproduce the fp16 product exactly.
+//   salient  v_mfma_f32_16x16x32_f16: the expert's fp16 tile as stored x the activations at its salient
+//            columns, converted bf16 -> fp16 by the preparation kernel after an exact per-token power-of-two
+//            scaling that keeps them inside the fp16 range.
 // Zero point and per-output-channel step are applied after the reduction:
 //   sum over non-salient i of x_i (u_i - z) = sum_all x_i u_i - z (sum_all x_i - sum_salient x_i),
 // (codes stored at salient and padding columns are 0), the bracket being a per-token number the
 // preparation kernel provides.
 //
 // Slots.  The host lists the experts that own tokens of the group ("slots", in expert order; an expert
-// with an empty segment is never touched).  The kernel walks slots in a compile-time unrolled loop so
-// that every code word lives in a fixed register; whether a slot has tokens in a given 16-token tile is
-// a wave-uniform test on a per-lane token->slot table.
+// with an empty segment is never touched).  Tokens are sorted by expert, so the slots with tokens in one
+// 16-token tile are a contiguous range, walked by a plain loop; the code words of the chunk wait in LDS,
+// where a run-time slot number can index them.
 #include "mes_internal.h"
 
+#ifndef MES_EXP
+#define MES_EXP 0
+#endif
 #ifdef MES_TRACE
 #include <cstdio>
 #include <cstdlib>
@@ -53,7 +58,7 @@ constexpr int kStageVec = 2048;                 // 16-byte slots of activations 
 constexpr int kStageBytes = kStageVec * 16 + 256;   // + one block scale per token
 constexpr int kStageFp8 = 16384;                // byte offset of the fp8 pieces inside a stage
 constexpr int kStageScale = 32768;              // byte offset of the scales inside a stage
-constexpr int kStageBlocks = 33;                // 1 KiB blocks the main kernel copies per chunk (the last one is partial)
+constexpr int kStageBlocks = 32;                // 1 KiB blocks the main kernel copies to LDS per chunk (the scales are read from memory)
 constexpr int kStageLds = kStageBlocks * 1024;  // LDS bytes of one stage
 constexpr int kMaxSlots = 16;                   // experts with tokens in one token group (the host cuts groups accordingly)
 constexpr int kMaxVisits = kMaxSlots + 3;       // (expert, 16-token tile) pairs in one group
@@ -64,8 +69,9 @@ struct LinearParams {
   const uint16_t* x;
   uint16_t* y;
   char* xt;         // workspace: one stage per chunk (see k_prepare)
-  u32x4* xs;        // workspace: salient activations per visit  [visit][k_pad/32][64 lanes]
+  u32x4* xs;        // workspace: salient activations per visit, fp16, scaled per token  [visit][k_pad/32][64 lanes]
   float* corr;      // workspace: per-token  z * (sum_all x - sum_salient x)  [64]
+  float* sal_scale; // workspace: per-token power of two the salient activations were divided by  [64]
   float* partial;   // workspace: [nsplit][64 tokens][d_out_pad] fp32 (split columns only)
   const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
@@ -74,7 +80,8 @@ struct LinearParams {
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
   uint8_t tok_slot[kTokGroup];            // slot of every token of the group, 0xFF past the last token
   uint8_t vis_slot[kMaxVisits + 1], vis_tt[kMaxVisits + 1];   // visits (slot, tile) in tile-major order
-  int d_in, d_out, d_out_pad, n_kb, n_chunks, n_jp, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
+  int tile_first[4], tile_last[4];        // slots that own tokens of 16-token tile tt: tile_first[tt] .. tile_last[tt]
+  int d_in, d_out, d_out_pad, n_chunks, n_jt, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
   float z;
 #ifdef MES_TRACE
   unsigned long long* trace;   // development builds only: [call][workgroup][16] timestamps
@@ -91,76 +98,66 @@ __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// fp4 (A, four registers) x fp8 E4M3 (B, eight registers), B scaled per lane by 2^(scale_b - 127).
-__device__ __forceinline__ f32x4 mfma_fp4_fp8(u32x4 a, v8i b, f32x4 c, int scale_b) {
-  const v8i a8 = {(int)a[0], (int)a[1], (int)a[2], (int)a[3], 0, 0, 0, 0};
-  return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a8, b, c, 4 /* A: fp4 */, 0 /* B: fp8 */, 0, 127, 0, scale_b);
+// acc += A x (Bhi + Blo) [+ Ah x (Bhi + Blo)], fp4 (A, four registers) x fp8 E4M3 (B, eight registers each),
+// B scaled per lane by 2^(scale_b - 127).  Written as instructions with the accumulator tied to itself: these
+// updates sit in loops and wave-uniform branches, and only a tied operand keeps the compiler from copying
+// whole accumulator sets from block to block.  The compiler does not know what the block contains, so the
+// block itself provides the two wait states the hardware needs between a vector-ALU write of an operand
+// register and a matrix instruction reading it.  (Same opcode, same register as source C and destination:
+// back-to-back issue needs no further wait states.)
+__device__ __forceinline__ void mfma_fp4_fp8_pair(f32x4& acc, u32x4 a, v8i bhi, v8i blo, int scale_b) {
+  asm volatile("s_nop 1\n\t"
+               "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4\n\t"
+               "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %3, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4"
+               : "+a"(acc) : "v"(a), "v"(bhi), "v"(blo), "v"(127), "v"(scale_b));
 }
 
-// Code words of one slot for one (row-tile pair, chunk): for each of the two row tiles LW low words and,
-// for b = 3, one word of high bits.
+// Code words of one slot for one (chunk, row tile): LW low words per lane and, for b = 3, one word of high bits.
 template <int BITS> struct Codec;
-template <> struct Codec<2> { static constexpr int LW = 2; static constexpr bool HI = false; };
-template <> struct Codec<1> { static constexpr int LW = 1; static constexpr bool HI = false; };
-template <> struct Codec<3> { static constexpr int LW = 2; static constexpr bool HI = true; };
+template <> struct Codec<2> { static constexpr int LW = 2; };
+template <> struct Codec<1> { static constexpr int LW = 1; };
+template <> struct Codec<3> { static constexpr int LW = 2; };
 
 template <int BITS>
 struct CodeRegs {
-  uint32_t lo[2][Codec<BITS>::LW];
-  uint32_t hi[2];
+  uint32_t lo[Codec<BITS>::LW];
+  uint32_t hi;
 };
 
-// Bytes of one (row-tile pair, chunk) block of a slot's codes.
-__host__ __device__ constexpr int code_block_bytes(int bits) { return bits == 1 ? 512 : bits == 2 ? 1024 : 1536; }
+// Bytes of one (chunk, row tile) block of a slot's codes.
+__host__ __device__ constexpr int code_block_bytes(int bits) { return 256 * bits; }
 
 template <int BITS>
-__device__ __forceinline__ void load_codes(const char* base, int jp, int c, int n_chunks, int lane, CodeRegs<BITS>& r) {
-  const char* blk = base + ((size_t)jp * n_chunks + c) * code_block_bytes(BITS);
-  if (BITS == 1) {
-    const u32x2 v = *reinterpret_cast<const u32x2*>(blk + lane * 8);
-    r.lo[0][0] = v[0]; r.lo[1][0] = v[1];
+__device__ __forceinline__ void load_codes(const char* blk, int lane, CodeRegs<BITS>& r) {
+  if constexpr (BITS == 1) {
+    r.lo[0] = *reinterpret_cast<const uint32_t*>(blk + lane * 4);
   } else {
-    const u32x4 v = *reinterpret_cast<const u32x4*>(blk + lane * 16);
-    r.lo[0][0] = v[0]; r.lo[0][Codec<BITS>::LW - 1] = v[1]; r.lo[1][0] = v[2]; r.lo[1][Codec<BITS>::LW - 1] = v[3];
-    if (BITS == 3) {
-      const u32x2 h = *reinterpret_cast<const u32x2*>(blk + 1024 + lane * 8);
-      r.hi[0] = h[0]; r.hi[1] = h[1];
-    }
+    const u32x2 v = *reinterpret_cast<const u32x2*>(blk + lane * 8);
+    r.lo[0] = v[0]; r.lo[1] = v[1];
+    if constexpr (BITS == 3) r.hi = *reinterpret_cast<const uint32_t*>(blk + 512 + lane * 4);
   }
 }
 
-// Low code bits of row tile rt as an fp4 A operand (values u / 2, or (u mod 4) / 2 for b = 3).
+// Low code bits as an fp4 A operand (values u / 2, or (u mod 4) / 2 for b = 3).
 template <int BITS>
-__device__ __forceinline__ u32x4 dequant_lo(const CodeRegs<BITS>& r, int rt) {
+__device__ __forceinline__ u32x4 dequant_lo(const CodeRegs<BITS>& r) {
   u32x4 a;
-  if (BITS == 1) {
-    const uint32_t w = r.lo[rt][0];
+  if constexpr (BITS == 1) {
+    const uint32_t w = r.lo[0];
     a[0] = w & 0x11111111u; a[1] = (w >> 1) & 0x11111111u; a[2] = (w >> 2) & 0x11111111u; a[3] = (w >> 3) & 0x11111111u;
   } else {
-    const uint32_t w0 = r.lo[rt][0], w1 = r.lo[rt][Codec<BITS>::LW - 1];
+    const uint32_t w0 = r.lo[0], w1 = r.lo[1];
     a[0] = w0 & 0x33333333u; a[1] = (w0 >> 2) & 0x33333333u; a[2] = w1 & 0x33333333u; a[3] = (w1 >> 2) & 0x33333333u;
   }
   return a;
 }
 
-// High code bit of row tile rt (b = 3) as an fp4 A operand: nibble 0h00 = 2 h = (4 h) / 2.
-__device__ __forceinline__ u32x4 dequant_hi(const CodeRegs<3>& r, int rt) {
-  const uint32_t w = r.hi[rt];
+// High code bit (b = 3) as an fp4 A operand: nibble 0h00 = 2 h = (4 h) / 2.
+__device__ __forceinline__ u32x4 dequant_hi(const CodeRegs<3>& r) {
+  const uint32_t w = r.hi;
   u32x4 a;
   a[0] = (w << 2) & 0x44444444u; a[1] = (w << 1) & 0x44444444u; a[2] = w & 0x44444444u; a[3] = (w >> 1) & 0x44444444u;
   return a;
-}
-
-// fp16 pair -> (bf16 hi pair, bf16 lo pair), value = hi + lo exactly.
-__device__ __forceinline__ void split_f16_pair(uint32_t w, uint32_t& hi, uint32_t& lo) {
-  const float f0 = (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
-  const float f1 = (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
-  const uint32_t h0 = __float_as_uint(f0) & 0xffff0000u;
-  const uint32_t h1 = __float_as_uint(f1) & 0xffff0000u;
-  const float l0 = f0 - __uint_as_float(h0);
-  const float l1 = f1 - __uint_as_float(h1);
-  hi = (h0 >> 16) | h1;
-  lo = (__float_as_uint(l0) >> 16) | (__float_as_uint(l1) & 0xffff0000u);
 }
 
 // fp32 -> bf16 bits, round to nearest even.
@@ -267,23 +264,40 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     return;
   }
   if (b < p.n_chunks + p.n_vis) {
+    // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
+    // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
+    // within 2^-29 of that largest one, and no value overflows.  The main kernel multiplies back.
     const int v = b - p.n_chunks;
     const int a = p.vis_slot[v], tt = p.vis_tt[v];
     const int32_t* si = p.sidx[a];
+    __shared__ uint32_t smax[16];
+    if (tid < 16) smax[tid] = 0;
+    __syncthreads();
+    const int lane = tid & 63, n = lane & 15, g = lane >> 4;
+    const int tl = 16 * tt + n;
+    const bool inm = tl >= p.lo[a] && tl < p.hi[a];
+    const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
+    uint32_t mymax = 0;
+    if (inm)
+      for (int r = tid >> 4; r < p.k; r += 16)   // indices are clamped so that a corrupt list can never address outside the row
+        mymax = max(mymax, (uint32_t)(xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))] & 0x7fffu));
+    if (mymax) atomicMax(&smax[tid & 15], mymax);   // (tid & 15) == n: the same token
+    __syncthreads();
+    int e = (int)(smax[n] >> 7) - 127 - 14;          // bf16 exponent field of the largest magnitude
+    if (smax[n] == 0) e = 0;
+    e = e < -110 ? -110 : (e > 110 ? 110 : e);
+    const float inv = __uint_as_float((uint32_t)(127 - e) << 23);
+    if (inm && tid < 16) p.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
     for (int i = tid; i < p.n_sb * 64; i += 256) {
-      const int sb = i >> 6, lane = i & 63, n = lane & 15, g = lane >> 4;
-      const int tl = 16 * tt + n;
-      const bool inm = tl >= p.lo[a] && tl < p.hi[a];
-      const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
+      const int sb = i >> 6;
       u32x4 o;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int r0 = 32 * sb + 8 * g + 2 * q;
-        uint32_t v0 = 0, v1 = 0;
-        // indices are clamped so that a corrupt list can never address outside the row
-        if (inm && r0 < p.k) v0 = xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))];
-        if (inm && r0 + 1 < p.k) v1 = xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))];
-        o[q] = v0 | (v1 << 16);
+        float v0 = 0.0f, v1 = 0.0f;
+        if (inm && r0 < p.k) v0 = bf16_to_f32(xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))]) * inv;
+        if (inm && r0 + 1 < p.k) v1 = bf16_to_f32(xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))]) * inv;
+        o[q] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v0) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v1) << 16);
       }
       p.xs[((size_t)v * p.n_sb + sb) * 64 + lane] = o;
     }
@@ -319,6 +333,14 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
 
 // ---- main kernel ------------------------------------------------------------------------------------
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ f32x4 mfma_f16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
 // Loads are written as (wave-uniform pointer) + (32-bit unsigned lane offset): the pointer then lives in
 // scalar registers and one vector register per lane serves every stream.
 __device__ __forceinline__ u32x4 ld128(const void* uniform_ptr, uint32_t lane_off) {
@@ -333,161 +355,163 @@ __device__ __forceinline__ v8i lds_fp8(const char* stage, int tt, int piece, int
   return v8i{(int)h0[0], (int)h0[1], (int)h0[2], (int)h0[3], (int)h1[0], (int)h1[1], (int)h1[2], (int)h1[3]};
 }
 
-// One (visit, 32-salient-column block) pair of the fp16 product.
-struct SalBuf {
-  u32x4 xs;
-  u32x4 d[2];
-};
-
-__device__ __forceinline__ void load_sal(const LinearParams& p, int pair, int lane, int jp, SalBuf& b) {
-  const int v = pair / p.n_sb, sb = pair - v * p.n_sb;
-  const int a = p.vis_slot[v];
-  b.xs = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)v * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-    b.d[rt] = ld128(p.sal[a] + ((size_t)(2 * jp + rt) * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
-}
-
-template <int TT>
-__device__ __forceinline__ void compute_sal(const LinearParams& p, int pair, const SalBuf& b, f32x4 (&acc_base)[2][TT]) {
-  const int tt_dyn = p.vis_tt[pair / p.n_sb];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    u32x4 dh, dl;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { uint32_t h, l; split_f16_pair(b.d[rt][q], h, l); dh[q] = h; dl[q] = l; }
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt)
-      if (tt == tt_dyn) {
-        acc_base[rt][tt] = mfma_bf16(dh, b.xs, acc_base[rt][tt]);
-        acc_base[rt][tt] = mfma_bf16(dl, b.xs, acc_base[rt][tt]);
-      }
-  }
-}
-
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void global_void;
-
 // Copies one chunk's stage from memory straight into LDS (no registers in between): wavefront `wave` of NW
-// copies the 1 KiB blocks wave, wave + NW, ... (33 blocks; block numbers past the last are clamped, which
-// rewrites the last block with the same bytes).  The number of copy instructions per wavefront is a
+// copies the 1 KiB blocks wave, wave + NW, ... of the 32.  The number of copy instructions per wavefront is a
 // compile-time constant, so the wait below can name exactly how many younger loads may still be in flight.
+// Written as instructions rather than through the compiler's builtin: the compiler would make every later
+// LDS access of the wavefront wait for these copies, i.e. stall each chunk for a full memory round trip,
+// because it cannot tell that they go to the stage nobody reads yet.  stage_barrier() does the waiting.
 template <int NW>
 __device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, int wave, int lane) {
-  constexpr int KD = (kStageBlocks + NW - 1) / NW;
+  static_assert(kStageBlocks % NW == 0, "the stage copy is dealt evenly to the wavefronts");
 #pragma unroll
-  for (int i = 0; i < KD; ++i) {
-    int blk = wave + NW * i;
-    blk = blk < kStageBlocks ? blk : kStageBlocks - 1;
-    __builtin_amdgcn_global_load_lds((global_void*)(src + blk * 1024 + lane * 16), (lds_void*)(dst_lds + blk * 1024), 16, 0, 0);
+  for (int i = 0; i < kStageBlocks / NW; ++i) {
+    const int blk = wave + NW * i;
+    const char* g = src + blk * 1024 + lane * 16;
+    const uint32_t l = (uint32_t)(uintptr_t)(dst_lds + blk * 1024);   // LDS byte address; the hardware adds 16 * lane
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
   }
-  asm volatile("" ::: "memory");   // later loads stay later: stage_barrier counts them
 }
 
-// vmcnt(n) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
-constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
+// vmcnt(n) lgkmcnt(0) (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at its maximum).
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070; }
 
 // Waits until at most `younger` of this wavefront's loads are in flight (loads complete in order, so the
 // stage copy issued before them has landed), for its LDS accesses, and then for the whole workgroup.
 // Deliberately not __syncthreads(): that would also wait for the weight loads of the next chunk.
 template <int YOUNGER>
 __device__ __forceinline__ void stage_barrier() {
-  __builtin_amdgcn_s_waitcnt(waitcnt_vm(YOUNGER) & ~0x0f00);   // vmcnt(YOUNGER) lgkmcnt(0)
+  __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(YOUNGER));
   asm volatile("s_barrier" ::: "memory");
 }
 
+// Per-wavefront state of the streaming loop.
+//  - Base weights are double buffered in registers: while chunk c is multiplied out of buffer c % 2, the
+//    4 KiB of chunk c + 1 are in flight into the other buffer.
+//  - Code words travel memory -> registers -> LDS.  Two register buffers hold the next two chunks' words;
+//    at the top of a chunk the buffer that has arrived is parked in the wavefront's private LDS area and
+//    reloaded at once with the chunk after next.  LDS can be indexed at run time, registers cannot: that
+//    is what lets the loop over the experts of a token tile be a plain loop with a run-time trip count.
 template <int BITS, int TT, int NA, int NW>
 struct Stream {
-  using C = Codec<BITS>;
-  static constexpr int kLoadsPerSlot = BITS == 3 ? 2 : 1;
-  static constexpr int kWeightLoads = 8 + NA * kLoadsPerSlot;   // per wavefront and chunk
-  static constexpr int kSlotsPerBase = NA / 4;                  // slots between two 32-column base blocks
+  static constexpr int kSlotLds = code_block_bytes(BITS);       // LDS bytes of one parked slot
+  static constexpr int kStageCopies = kStageBlocks / NW;        // copy instructions per wavefront and chunk
 
   const LinearParams& p;
-  int lane, n, jp;
-  const char* base_ptr;
-  size_t base_rt_stride;
+  int lane, n, jt;
+  char* park;                 // this wavefront's LDS area: [NA][kSlotLds]
   uint32_t slot_tok[TT];
+  int scale[2][TT];           // per-token block scales of the current / next chunk
   u32x4 base[2][4];
-  CodeRegs<BITS> code[NA];
-  f32x4 acc_base[2][TT], acc_raw[2][TT];
+  CodeRegs<BITS> code[2][NA];
+  f32x4 acc_base[TT], acc_raw[TT];
 
-  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jp_) : p(p_), lane(lane_), n(lane_ & 15), jp(jp_) {
-    base_ptr = p.w_base + (size_t)(2 * jp) * p.n_kb * 1024 + lane * 16;
-    base_rt_stride = (size_t)p.n_kb * 1024;
+  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jt_, char* park_) : p(p_), lane(lane_), n(lane_ & 15), jt(jt_), park(park_) {
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) slot_tok[tt] = p.tok_slot[16 * tt + n];
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) { acc_base[rt][tt] = f32x4{0, 0, 0, 0}; acc_raw[rt][tt] = f32x4{0, 0, 0, 0}; }
+    for (int tt = 0; tt < TT; ++tt) {
+      slot_tok[tt] = p.tok_slot[16 * tt + n];
+      acc_base[tt] = f32x4{0, 0, 0, 0};
+      acc_raw[tt] = f32x4{0, 0, 0, 0};
+    }
   }
 
-  __device__ __forceinline__ void load_base(int c, int kb) {
+  template <int BUF>
+  __device__ __forceinline__ void load_base(int c) {
+    const char* src = p.w_base + ((size_t)c * p.n_jt + jt) * 4096 + lane * 16;
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) base[rt][kb] = *reinterpret_cast<const u32x4*>(base_ptr + rt * base_rt_stride + (size_t)(4 * c + kb) * 1024);
+    for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
   }
 
-  __device__ __forceinline__ void load_all(int c) {
+  template <int BUF>
+  __device__ __forceinline__ void load_scales(int c) {
+    const int* src = reinterpret_cast<const int*>(p.xt + (size_t)c * kStageBytes + kStageScale);
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) load_base(c, kb);
-#pragma unroll
-    for (int a = 0; a < NA; ++a) load_codes<BITS>(p.codes[a], jp, c, p.n_chunks, lane, code[a]);
+    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = src[16 * tt + n];
   }
 
-  // One chunk: its activations are in `cur`; the next chunk's are copied into `nxt` meanwhile.  Every weight
-  // register is reloaded with the next chunk's data right after its last use, so all of a wavefront's
-  // weight bytes for one chunk are in flight or waiting in registers at any time.
-  __device__ __forceinline__ void chunk(int c, int cn, const char* cur, char* nxt, int wave) {
-    stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
-    int scale_tok[TT];
+  template <int BUF>
+  __device__ __forceinline__ void load_code_regs(int c) {
+    const size_t off = ((size_t)c * p.n_jt + jt) * kSlotLds;
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) scale_tok[tt] = *reinterpret_cast<const int*>(cur + kStageScale + (16 * tt + n) * 4);
-    int bcur = -1;
-    v8i bhi = {0, 0, 0, 0, 0, 0, 0, 0}, blo = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int a = 0; a < NA; ++a) load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
+  }
+
+  // Register buffer BUF -> this wavefront's LDS area, then the buffer is reloaded with chunk `c2` (two chunks
+  // ahead: the other buffer holds the chunk in between, already in flight).
+  template <int BUF>
+  __device__ __forceinline__ void park_and_reload(int c2) {
+    const size_t off = ((size_t)c2 * p.n_jt + jt) * kSlotLds;
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
-      if (a % kSlotsPerBase == 0) {   // a 32-column block of the base product between groups of slots
-        const int kb = a / kSlotsPerBase;
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-          const u32x4 xb = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
-#pragma unroll
-          for (int rt = 0; rt < 2; ++rt) acc_base[rt][tt] = mfma_bf16(base[rt][kb], xb, acc_base[rt][tt]);
-        }
-        load_base(cn, kb);
+      char* dst = park + a * kSlotLds;
+      const CodeRegs<BITS>& r = code[BUF][a];
+      if constexpr (BITS == 1) {
+        *reinterpret_cast<uint32_t*>(dst + lane * 4) = r.lo[0];
+      } else {
+        *reinterpret_cast<u32x2*>(dst + lane * 8) = u32x2{r.lo[0], r.lo[1]};
+        if constexpr (BITS == 3) *reinterpret_cast<uint32_t*>(dst + 512 + lane * 4) = r.hi;
       }
-      u32x4 dq[2], dqh[2];
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        dq[rt] = dequant_lo<BITS>(code[a], rt);
-        if constexpr (BITS == 3) dqh[rt] = dequant_hi(code[a], rt);
-      }
-      load_codes<BITS>(p.codes[a], jp, cn, p.n_chunks, lane, code[a]);
-#pragma unroll
-      for (int tt = 0; tt < TT; ++tt) {
-        const bool mine = slot_tok[tt] == (uint32_t)a;
-        if (__builtin_amdgcn_ballot_w64(mine) != 0) {
-          if (bcur != tt) {
-            bhi = lds_fp8(cur, tt, 0, lane);
-            blo = lds_fp8(cur, tt, 1, lane);
-            bcur = tt;
-          }
-          const int sc = mine ? scale_tok[tt] : 0;
-          acc_raw[0][tt] = mfma_fp4_fp8(dq[0], bhi, acc_raw[0][tt], sc);
-          acc_raw[1][tt] = mfma_fp4_fp8(dq[1], bhi, acc_raw[1][tt], sc);
-          acc_raw[0][tt] = mfma_fp4_fp8(dq[0], blo, acc_raw[0][tt], sc);
-          acc_raw[1][tt] = mfma_fp4_fp8(dq[1], blo, acc_raw[1][tt], sc);
-          if constexpr (BITS == 3) {
-            acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], bhi, acc_raw[0][tt], sc);
-            acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], bhi, acc_raw[1][tt], sc);
-            acc_raw[0][tt] = mfma_fp4_fp8(dqh[0], blo, acc_raw[0][tt], sc);
-            acc_raw[1][tt] = mfma_fp4_fp8(dqh[1], blo, acc_raw[1][tt], sc);
-          }
-        }
-      }
+      load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
     }
-    stage_barrier<kWeightLoads>();
+  }
+
+  __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
+    CodeRegs<BITS> r;
+    load_codes<BITS>(park + a * kSlotLds, lane, r);
+    return r;
+  }
+
+  // Loads of one chunk() call that are younger than its stage copy.
+  static constexpr int kYounger = 4 + TT;
+
+  // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
+  template <int BUF>
+  __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave, bool tr = false) {
+#ifdef MES_TRACE
+#define MES_CSTAMP(i) do { if (tr) MES_STAMP(i); } while (0)
+#else
+#define MES_CSTAMP(i) do { } while (0)
+#endif
+    MES_CSTAMP(2);
+#if MES_EXP == 2
+    cn = 0; c2 = 0;
+#endif
+    park_and_reload<BUF>(c2);
+    stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
+    load_base<BUF ^ 1>(cn);
+    load_scales<BUF ^ 1>(cn);
+    MES_CSTAMP(3);
+#if MES_EXP == 3
+    // loads only: keep the loaded registers alive without any arithmetic
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) asm volatile("" : : "v"(base[BUF][kb]));
+    if (false)
+#endif
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const v8i bhi = lds_fp8(cur, tt, 0, lane), blo = lds_fp8(cur, tt, 1, lane);
+      const int first = p.tile_first[tt], last = p.tile_last[tt];
+      CodeRegs<BITS> cr = parked(first);
+      u32x4 xb[4];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
+      for (int a = first; a <= last; ++a) {
+        const int sc = slot_tok[tt] == (uint32_t)a ? scale[BUF][tt] : 0;
+        const u32x4 d = dequant_lo<BITS>(cr);
+        u32x4 h;
+        if constexpr (BITS == 3) h = dequant_hi(cr);
+        cr = parked(a < last ? a + 1 : a);   // the next visit's words, fetched while this one multiplies
+        mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
+        if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
+      }
+      MES_CSTAMP(4 + tt);
+    }
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(kYounger));
+    MES_CSTAMP(8);
+    stage_barrier<kYounger>();
+    MES_CSTAMP(9);
   }
 };
 
@@ -500,88 +524,121 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int rg = blockIdx.x, sp = blockIdx.y;
-  int jp = rg * NW + wave;
-  const bool live = jp < p.n_jp;            // wavefronts past the last row tile pair recompute the last one and store nothing
-  jp = live ? jp : p.n_jp - 1;
+  int jt = rg * NW + wave;
+  const bool live = jt < p.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
+  jt = live ? jt : p.n_jt - 1;
   const int c_begin = (int)((long)sp * p.n_chunks / p.nsplit);
   const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
   MES_STAMP(0);
 
-  // two stages, as two arrays: the compiler then knows that a copy into one never touches what is read from the other
+  // two stages, as two arrays: a copy into one never touches what is read from the other
   __shared__ __attribute__((aligned(16))) char stage0[kStageLds];
   __shared__ __attribute__((aligned(16))) char stage1[kStageLds];
+  // parked code words: one private area per wavefront
+  __shared__ __attribute__((aligned(16))) char park_all[NW * NA * code_block_bytes(BITS)];
 
-  Stream<BITS, TT, NA, NW> ws(p, lane, jp);
-  f32x4 (&acc_base)[2][TT] = ws.acc_base;
-  f32x4 (&acc_raw)[2][TT] = ws.acc_raw;
+  using S = Stream<BITS, TT, NA, NW>;
+  S ws(p, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)));
+  f32x4 (&acc_base)[TT] = ws.acc_base;
+  f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
 
-  // prologue: first chunk's activations into stage 0, its weights into registers
-  stage_copy<NW>(p.xt + (size_t)c_begin * kStageBytes, stage0, wave, lane);
-  ws.load_all(c_begin);
-  stage_barrier<Stream<BITS, TT, NA, NW>::kWeightLoads>();
-  MES_STAMP(1);
-  for (int c = c_begin; c < c_end; c += 2) {
-    ws.chunk(c, c + 1 < c_end ? c + 1 : c, stage0, stage1, wave);
-    if (c - c_begin < 10) MES_STAMP(2 + c - c_begin);
-    if (c + 1 >= c_end) break;
-    ws.chunk(c + 1, c + 2 < c_end ? c + 2 : c + 1, stage1, stage0, wave);
-    if (c + 1 - c_begin < 10) MES_STAMP(3 + c - c_begin);
+  // The chunks of the range are visited from a start that differs from row group to row group (the sum
+  // does not care about the order), so that workgroups running side by side do not march in lockstep
+  // through the same columns.
+  const int len = c_end - c_begin;
+  const int rot = len > 0 ? (int)((((uint32_t)rg * 2654435761u) >> 12) % (uint32_t)len) : 0;
+  auto chunk_at = [&](int i) { i = i < len ? i : len - 1; int r = i + rot; r = r >= len ? r - len : r; return c_begin + r; };
+  // first chunks' activations and weights: requested now, needed after the salient product below
+  stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
+  ws.template load_base<0>(chunk_at(0));
+  ws.template load_scales<0>(chunk_at(0));
+  ws.template load_code_regs<0>(chunk_at(0));
+  ws.template load_code_regs<1>(chunk_at(1));
+
+  // what the epilogue needs from memory, requested early: the owning expert's step per output channel
+  // and the zero-point correction per token
+  f32x4 stepv[TT];
+  float corr[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    const int tl = 16 * tt + n;
+    const uint32_t at = slot_tok[tt];
+    corr[tt] = sp == 0 ? p.corr[tl] : 0.0f;   // belongs to the whole column range: only the first split applies it
+    const int j = 16 * jt + 4 * g;
+    stepv[tt] = f32x4{0, 0, 0, 0};
+    if (at != 0xffu && j < p.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(p.step[at] + j);
   }
 
+  // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits, four pairs
+  // of loads in flight.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
   MES_STAMP(12);
-  // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits; the
-  // wavefront prefetches its next pair while it multiplies the current one
-  MES_STAMP(12);
+  f32x4 acc_sal[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) acc_sal[tt] = f32x4{0, 0, 0, 0};
   if (p.k > 0) {
+    constexpr int SD = 4;
     const int n_pairs = p.n_vis * p.n_sb;
-    const int stride = p.nsplit;
-    int pair = sp;
-    if (pair < n_pairs) {
-      SalBuf sa, sb;
-      load_sal(p, pair, lane, jp, sa);
-      while (true) {
-        const int nx = pair + stride;
-        load_sal(p, nx < n_pairs ? nx : pair, lane, jp, sb);
-        compute_sal<TT>(p, pair, sa, acc_base);
-        if (nx >= n_pairs) break;
-        pair = nx;
-        const int nx2 = pair + stride;
-        load_sal(p, nx2 < n_pairs ? nx2 : pair, lane, jp, sa);
-        compute_sal<TT>(p, pair, sb, acc_base);
-        if (nx2 >= n_pairs) break;
-        pair = nx2;
+    const int mine = (n_pairs - sp + p.nsplit - 1) / p.nsplit;   // pairs sp, sp + nsplit, ...
+    u32x4 sx[SD], sd[SD];
+    auto load_pair = [&](int i, u32x4& x, u32x4& d) {
+      const int pair = sp + (i < mine ? i : mine - 1) * p.nsplit;
+      const int v = pair / p.n_sb, sb = pair - v * p.n_sb;
+      const int a = p.vis_slot[v];
+      x = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)v * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
+      d = ld128(p.sal[a] + ((size_t)jt * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
+    };
+    if (mine > 0) {
+#pragma unroll
+      for (int i = 0; i < SD; ++i) load_pair(i, sx[i], sd[i]);
+      for (int i0 = 0; i0 < mine; i0 += SD) {
+#pragma unroll
+        for (int i = 0; i < SD; ++i) {
+          if (i0 + i < mine) {
+            const int tt_dyn = p.vis_tt[(sp + (i0 + i) * p.nsplit) / p.n_sb];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+              if (tt == tt_dyn) acc_sal[tt] = mfma_f16(sd[i], sx[i], acc_sal[tt]);
+          }
+          load_pair(i0 + i + SD, sx[i], sd[i]);
+        }
       }
     }
   }
-
-  // epilogue: remove the zero point, apply the expert's step
   MES_STAMP(13);
+  // the salient product starts the base accumulators (the scale is an exact power of two)
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) acc_base[tt] = acc_sal[tt] * p.sal_scale[16 * tt + n];
+
+  stage_barrier<0>();
+  MES_STAMP(1);
+  for (int i = 0; i < len; i += 2) {
+    ws.template chunk<0>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
+    if (i + 1 >= len) break;
+    ws.template chunk<1>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+  }
+
+  // epilogue: remove the zero point, apply the expert's step (the salient product is already in acc_base).
+  // The last matrix instructions above were issued from an assembly block: give them the wait states a
+  // matrix result needs before vector instructions may read it.
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   if (!live) return;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     const int tl = 16 * tt + n, t = p.t0 + tl;
-    const uint32_t at = slot_tok[tt];
-    // the correction belongs to the whole column range: only the first split applies it
-    const float cr = sp == 0 ? p.corr[tl] : 0.0f;
+    const int j = 16 * jt + 4 * g;
+    f32x4 o;
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      const int j = 32 * jp + 16 * rt + 4 * g;
-      f32x4 st = {0, 0, 0, 0};
-      if (at != 0xffu && j < p.d_out) st = *reinterpret_cast<const f32x4*>(p.step[at] + j);
-      f32x4 o;
-#pragma unroll
-      for (int v = 0; v < 4; ++v) o[v] = acc_base[rt][tt][v] + st[v] * (acc_raw[rt][tt][v] - cr);
-      if (p.nsplit == 1) {
-        if (t < p.T && j < p.d_out) {
-          uint2 pk;
-          pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
-          pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-          *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
-        }
-      } else {
-        *reinterpret_cast<f32x4*>(p.partial + ((size_t)(sp * kTokGroup + tl) * p.d_out_pad + j)) = o;
+    for (int v = 0; v < 4; ++v) o[v] = acc_base[tt][v] + stepv[tt][v] * (acc_raw[tt][v] - corr[tt]);
+    if (p.nsplit == 1) {
+      if (t < p.T && j < p.d_out) {
+        uint2 pk;
+        pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+        pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+        *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
       }
+    } else {
+      *reinterpret_cast<f32x4*>(p.partial + ((size_t)(sp * kTokGroup + tl) * p.d_out_pad + j)) = o;
     }
   }
   MES_STAMP(14);
@@ -602,39 +659,35 @@ __global__ __launch_bounds__(256) void k_reduce_splits(const LinearParams p, int
   *reinterpret_cast<uint2*>(p.y + (size_t)(p.t0 + tl) * p.d_out + j) = pk;
 }
 
-constexpr int kMaxPassSlots = 16;   // active experts one launch handles (its code words live in registers)
+// Active experts one launch handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
+// 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
+constexpr int max_pass_slots(int bits) { return bits == 3 ? 10 : 16; }
+
+constexpr int kWaves = 8;   // wavefronts per workgroup; each owns 16 output channels
 
 struct Plan {
-  int nw;      // wavefronts per workgroup; each owns 32 output channels
   int nsplit;  // workgroups that share one row group's columns
 };
 
 // Pure function of the layer shape (not of bits or T), so the workspace size is known up front.
-// One workgroup runs per compute unit (256 of them): the shape's row tile pairs are grouped NW to a
-// workgroup and the chunks split over `nsplit` workgroups so that the grid comes as close as possible to
-// a whole number of rounds of 256, with at least four chunks per workgroup and few splits (every split
-// writes and re-reads a partial output tile).
+// One workgroup runs per compute unit (256 of them).  The chunks are split over `nsplit` workgroups so that
+// the grid fills the largest part of the last round of 256, with at least four chunks per workgroup and,
+// among equals, few splits (every split writes and re-reads a partial output tile).
 Plan plan_for(int d_in, int d_out) {
-  const int n_jp = ceil_to(d_out, kRowPad) / 32, n_chunks = ceil_to(d_in, kColPad) / kChunk;
+  const int n_jt = ceil_to(d_out, kRowPad) / 16, n_chunks = ceil_to(d_in, kColPad) / kChunk;
 #ifdef MES_TRACE
-  if (const char* ov = getenv("MES_PLAN")) { Plan o{4, 1}; if (sscanf(ov, "%d,%d", &o.nw, &o.nsplit) == 2) return o; }
+  if (const char* ov = getenv("MES_PLAN")) { Plan o{1}; if (sscanf(ov, "%d", &o.nsplit) == 1) return o; }
 #endif
-  static const int kNw[] = {4, 2, 1};
-  Plan best{4, 1};
+  const int rgs = (n_jt + kWaves - 1) / kWaves;
+  Plan best{1};
   double best_cost = 1e30;
-  for (int nw : kNw) {
-    const int rgs = (n_jp + nw - 1) / nw;
-    for (int ns = 1; ns <= 32 && ns * 4 <= (n_chunks < 4 ? 4 : n_chunks); ++ns) {
-      const long wgs = (long)rgs * ns;
-      const long rounds = (wgs + 255) / 256;
-      const int chunks_wg = (n_chunks + ns - 1) / ns;
-      // time ~ rounds x (chunks per workgroup + fixed start-up/finish cost in chunk units), at a per-unit rate
-      // that improves with the number of wavefronts of a unit sharing one staged activation chunk
-      const double per_chunk = nw * 1.0 + 1.5;                 // weight bytes + activation copy, relative
-      double cost = (double)rounds * (chunks_wg * per_chunk + 6.0 * (nw < 4 ? 4 : nw) / 4.0);
-      cost += ns > 1 ? 0.35 * ns : 0.0;                        // partial tiles: written, then read by the reduction
-      if (cost < best_cost) { best_cost = cost; best = Plan{nw, ns}; }
-    }
+  for (int ns = 1; ns <= 32 && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
+    const long wgs = (long)rgs * ns;
+    const long rounds = (wgs + 255) / 256;
+    const int chunks_wg = (n_chunks + ns - 1) / ns;
+    // time ~ rounds x (chunks per workgroup + a fixed start/finish cost of about three chunks) + the partial tiles
+    const double cost = (double)rounds * (chunks_wg + 3.0) + (ns > 1 ? 0.25 * ns : 0.0);
+    if (cost < best_cost) { best_cost = cost; best = Plan{ns}; }
   }
   return best;
 }
@@ -650,35 +703,26 @@ WorkspaceLayout workspace_layout(int d_in, int d_out) {
   size_t off = 0;
   w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes + 1024;   // the copy of the last stage's partial block reads a full KiB
   w.xs = off;      off += (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
-  w.corr = off;    off += 256;
+  w.corr = off;    off += 512;   // corrections, then salient scales
   w.partial = off; off += pl.nsplit > 1 ? (size_t)pl.nsplit * kTokGroup * po * sizeof(float) : 0;
   w.total = off;
   return w;
 }
 
-template <int BITS, int TT, int NA>
-hipError_t launch_nw(const LinearParams& p, int nw, dim3 grid, hipStream_t s) {
-  switch (nw) {
-    case 1: k_delta_linear<BITS, TT, NA, 1><<<grid, 64, 0, s>>>(p); break;
-    case 2: k_delta_linear<BITS, TT, NA, 2><<<grid, 128, 0, s>>>(p); break;
-    default: k_delta_linear<BITS, TT, NA, 4><<<grid, 256, 0, s>>>(p); break;
+template <int BITS, int NA>
+hipError_t launch_tt(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
+  switch (tt) {
+    case 1: k_delta_linear<BITS, 1, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
+    case 2: k_delta_linear<BITS, 2, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
+    default: k_delta_linear<BITS, 4, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
   }
   return hipGetLastError();
 }
 
-template <int BITS, int NA>
-hipError_t launch_tt(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
-  switch (tt) {
-    case 1: return launch_nw<BITS, 1, NA>(p, nw, grid, s);
-    case 2: return launch_nw<BITS, 2, NA>(p, nw, grid, s);
-    default: return launch_nw<BITS, 4, NA>(p, nw, grid, s);
-  }
-}
-
 template <int BITS>
-hipError_t launch_na(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
-  if (p.n_act <= 4) return launch_tt<BITS, 4>(p, tt, nw, grid, s);
-  return launch_tt<BITS, kMaxPassSlots>(p, tt, nw, grid, s);
+hipError_t launch_na(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
+  if (p.n_act <= 4) return launch_tt<BITS, 4>(p, tt, grid, s);
+  return launch_tt<BITS, max_pass_slots(BITS)>(p, tt, grid, s);
 }
 
 }  // namespace
@@ -710,31 +754,32 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.xt = ws + wl.xt;
   p.xs = reinterpret_cast<u32x4*>(ws + wl.xs);
   p.corr = reinterpret_cast<float*>(ws + wl.corr);
+  p.sal_scale = p.corr + kTokGroup;
   p.partial = reinterpret_cast<float*>(ws + wl.partial);
   const int po = ceil_to(d0.d_out, kRowPad), pi = ceil_to(d0.d_in, kColPad);
   p.d_in = d0.d_in;
   p.d_out = d0.d_out;
   p.d_out_pad = po;
-  p.n_kb = pi / 32;
   p.n_chunks = pi / kChunk;
-  p.n_jp = po / 32;
+  p.n_jt = po / 16;
   p.n_sb = ceil_to(d0.k, kSalPad) / 32;
   p.k = d0.k;
   p.T = c.T;
   p.nsplit = pl.nsplit;
   p.bits = d0.bits;
   p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
-  const dim3 grid((p.n_jp + pl.nw - 1) / pl.nw, pl.nsplit);
-  // Token groups: up to 64 consecutive tokens that belong to at most kMaxPassSlots experts.
+  const dim3 grid((p.n_jt + kWaves - 1) / kWaves, pl.nsplit);
+  // Token groups: up to 64 consecutive tokens that belong to at most max_pass_slots experts.
+  const int max_slots = max_pass_slots(d0.bits);
   int e_cur = 0;   // first expert that may own token t0
   for (int t0 = 0; t0 < c.T;) {
     while (c.seg[e_cur + 1] <= t0) ++e_cur;
     int nt = c.T - t0 < kTokGroup ? c.T - t0 : kTokGroup;
-    {   // cut the group where the (kMaxPassSlots + 1)-th active expert would start
+    {   // cut the group where one expert too many would start
       int act = 0;
       for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
         if (c.seg[e + 1] <= c.seg[e]) continue;
-        if (++act > kMaxPassSlots) { nt = c.seg[e] - t0; break; }
+        if (++act > max_slots) { nt = c.seg[e] - t0; break; }
       }
     }
     p.t0 = t0;
@@ -755,7 +800,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       for (int tl = lo; tl < hi; ++tl) p.tok_slot[tl] = (uint8_t)na;
       ++na;
     }
-    for (int a = na; a < kMaxPassSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
+    for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
       p.codes[a] = p.codes[0]; p.step[a] = p.step[0]; p.sal[a] = p.sal[0]; p.sidx[a] = p.sidx[0];
       p.lo[a] = 0; p.hi[a] = 0;
     }
@@ -771,6 +816,11 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
         ++nv;
       }
     for (int v = nv; v <= kMaxVisits; ++v) { p.vis_slot[v] = 0; p.vis_tt[v] = 0; }
+    for (int t = 0; t < 4; ++t) {
+      p.tile_first[t] = 0; p.tile_last[t] = 0;
+      const int tl0 = 16 * t, tl1 = 16 * t + 15 < nt - 1 ? 16 * t + 15 : nt - 1;
+      if (tl0 < nt) { p.tile_first[t] = p.tok_slot[tl0]; p.tile_last[t] = p.tok_slot[tl1]; }
+    }
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
     p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
@@ -778,9 +828,9 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     switch (d0.bits) {
-      case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
-      case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
-      default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
+      case 1: e = launch_na<1>(p, tt, grid, s); break;
+      case 2: e = launch_na<2>(p, tt, grid, s); break;
+      default: e = launch_na<3>(p, tt, grid, s); break;
     }
     if (e != hipSuccess) return e;
     if (pl.nsplit > 1) {

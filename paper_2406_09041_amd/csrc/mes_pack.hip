@@ -45,12 +45,16 @@ __global__ void k_pack_base(const uint16_t* __restrict__ w, int d_in, int d_out,
                             uint4* __restrict__ out) {
   size_t slot = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (slot >= n_slots) return;
+  // slot = ((c * n_jt + jt) * 4 + kb) * 64 + lane: chunk-major
   int lane = (int)(slot & 63);
   size_t blk = slot >> 6;
-  int kb = (int)(blk % n_kb);
-  int jt = (int)(blk / n_kb);
+  int kb = (int)(blk & 3);
+  blk >>= 2;
+  const int n_jt = (d_out + 63) / 64 * 4;
+  int jt = (int)(blk % n_jt);
+  int c = (int)(blk / n_jt);
   int row = 16 * jt + (lane & 15);
-  int col = 32 * kb + 8 * (lane >> 4);
+  int col = 128 * c + 32 * kb + 8 * (lane >> 4);
   uint4 v = make_uint4(0, 0, 0, 0);
   if (row < d_out && col < d_in) v = *reinterpret_cast<const uint4*>(w + (size_t)row * d_in + col);
   out[slot] = v;
@@ -62,10 +66,13 @@ __global__ void k_unpack_base(const uint4* __restrict__ t, int d_in, int d_out, 
   if (slot >= n_slots) return;
   int lane = (int)(slot & 63);
   size_t blk = slot >> 6;
-  int kb = (int)(blk % n_kb);
-  int jt = (int)(blk / n_kb);
+  int kb = (int)(blk & 3);
+  blk >>= 2;
+  const int n_jt = (d_out + 63) / 64 * 4;
+  int jt = (int)(blk % n_jt);
+  int c = (int)(blk / n_jt);
   int row = 16 * jt + (lane & 15);
-  int col = 32 * kb + 8 * (lane >> 4);
+  int col = 128 * c + 32 * kb + 8 * (lane >> 4);
   if (row < d_out && col < d_in) *reinterpret_cast<uint4*>(w + (size_t)row * d_in + col) = t[slot];
 }
 
@@ -115,8 +122,8 @@ __global__ void k_row_step(const float* __restrict__ delta, int d_in, const int3
   }
 }
 
-// Where the code of (row, col) is stored (see mes.h, "codes").  Blocks of 32 rows x 128 columns; inside a
-// block lane = 16 g + r owns, for each of its two 16-row tiles rt, the 32 columns 32 g + e, e = 8 q + pp.
+// Where the code of (row, col) is stored (see mes.h, "codes").  Blocks of 16 rows x 128 columns, chunk-major;
+// inside a block lane = 16 g + r owns the 32 columns 32 g + e, e = 8 q + pp.
 struct CodeLoc {
   size_t lo_word;   // index of the 32-bit word holding the low bits (all bits for b = 1, 2)
   int lo_shift;
@@ -124,20 +131,20 @@ struct CodeLoc {
   int hi_shift;
 };
 
-__device__ __forceinline__ CodeLoc code_location(int bits, int n_chunks, int row, int col) {
-  const int jp = row >> 5, rt = (row >> 4) & 1, r = row & 15;
+__device__ __forceinline__ CodeLoc code_location(int bits, int n_jt, int row, int col) {
+  const int jt = row >> 4, r = row & 15;
   const int c = col >> 7, g = (col >> 5) & 3, e = col & 31, q = e >> 3, pp = e & 7;
   const int lane = 16 * g + r;
-  const size_t blk = ((size_t)jp * n_chunks + c) * (bits == 1 ? 128 : bits == 2 ? 256 : 384);
+  const size_t blk = ((size_t)c * n_jt + jt) * (64 * bits);
   CodeLoc L;
   if (bits == 1) {
-    L.lo_word = blk + lane * 2 + rt;
+    L.lo_word = blk + lane;
     L.lo_shift = 4 * pp + q;
     L.hi_word = 0; L.hi_shift = 0;
   } else {
-    L.lo_word = blk + lane * 4 + rt * 2 + (q >> 1);
+    L.lo_word = blk + lane * 2 + (q >> 1);
     L.lo_shift = 4 * pp + 2 * (q & 1);
-    L.hi_word = blk + 256 + lane * 2 + rt;
+    L.hi_word = blk + 128 + lane;
     L.hi_shift = 4 * pp + q;
   }
   return L;
@@ -146,7 +153,7 @@ __device__ __forceinline__ CodeLoc code_location(int bits, int n_chunks, int row
 // One thread per (row, 8 consecutive columns): quantise and OR the codes into their words (the buffer was
 // zeroed before; words are shared by threads, hence atomicOr).
 __global__ void k_pack_codes(const float* __restrict__ delta, int d_in, int d_out, const int32_t* __restrict__ sidx,
-                             int k, int bits, int grid, const float* __restrict__ step, int n_chunks,
+                             int k, int bits, int grid, const float* __restrict__ step, int n_jt,
                              uint32_t* __restrict__ out) {
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int groups = d_in / 8;
@@ -155,12 +162,12 @@ __global__ void k_pack_codes(const float* __restrict__ delta, int d_in, int d_ou
   const float s = step[row];
   const float* r = delta + (size_t)row * d_in;
   uint32_t lo_bits = 0, hi_bits = 0;
-  const CodeLoc L0 = code_location(bits, n_chunks, row, col0);   // the 8 columns share both words
+  const CodeLoc L0 = code_location(bits, n_jt, row, col0);   // the 8 columns share both words
   for (int pp = 0; pp < 8; ++pp) {
     const int col = col0 + pp;
     if (is_salient(sidx, k, col, nullptr)) continue;
     const uint32_t u = quant_code(r[col], s, bits, grid);
-    const CodeLoc L = code_location(bits, n_chunks, row, col);
+    const CodeLoc L = code_location(bits, n_jt, row, col);
     lo_bits |= (bits == 3 ? (u & 3u) : u) << L.lo_shift;
     if (bits == 3) hi_bits |= (u >> 2) << L.hi_shift;
   }
@@ -192,8 +199,8 @@ __global__ void k_pack_salient(const float* __restrict__ delta, int d_in, int d_
   out[idx] = v;
 }
 
-__device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, int n_chunks, int row, int col) {
-  const CodeLoc L = code_location(bits, n_chunks, row, col);
+__device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, int n_jt, int row, int col) {
+  const CodeLoc L = code_location(bits, n_jt, row, col);
   if (bits == 1) return (codes[L.lo_word] >> L.lo_shift) & 1u;
   const uint32_t lo = (codes[L.lo_word] >> L.lo_shift) & 3u;
   if (bits == 2) return lo;
@@ -304,9 +311,9 @@ hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int3
   k_row_step<<<d_out, 256, 0, s>>>(delta, d_in, sidx, k, bits, grid, policy, step_in, step_out);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
-  const int n_chunks = pi / 128;
+  const int n_jt = po / 16;
   if ((e = launch_fill_zero(codes, (size_t)po * pi * bits / 8, s)) != hipSuccess) return e;
-  k_pack_codes<<<blocks_for((size_t)d_out * (d_in / 8), 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, bits, grid, step_out, n_chunks, codes);
+  k_pack_codes<<<blocks_for((size_t)d_out * (d_in / 8), 256), 256, 0, s>>>(delta, d_in, d_out, sidx, k, bits, grid, step_out, n_jt, codes);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (k > 0) {
     int n_sb = ceil_to(k, kSalPad) / 32;
@@ -319,7 +326,7 @@ hipError_t launch_pack_delta(const float* delta, int d_in, int d_out, const int3
 
 hipError_t launch_unpack_delta(const mes_delta& d, float* delta_hat, uint8_t* codes_out, hipStream_t s) {
   int pi = ceil_to(d.d_in, kColPad);
-  int n_ks = pi / 128;
+  int n_ks = ceil_to(d.d_out, kRowPad) / 16;   // row tiles
   int n_sb = ceil_to(d.k, kSalPad) / 32;
   size_t n = (size_t)d.d_in * d.d_out;
   k_unpack_delta<<<blocks_for(n, 256), 256, 0, s>>>(reinterpret_cast<const uint32_t*>(d.codes), d.step,

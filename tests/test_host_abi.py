@@ -23,7 +23,7 @@ def test_every_declared_symbol_is_exported():
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
-    assert lib.mes_layout_version() == 2
+    assert lib.mes_layout_version() == 3
 
 
 def test_size_functions_match_the_layout_specification():
@@ -81,7 +81,7 @@ def test_select_argument_errors():
 
 
 def _desc(**kw):
-    d = dict(d_in=64, d_out=64, k=4, bits=2, grid=0, layout_version=2, codes=FAKE, step=FAKE, salient=FAKE, salient_idx=FAKE)
+    d = dict(d_in=64, d_out=64, k=4, bits=2, grid=0, layout_version=3, codes=FAKE, step=FAKE, salient=FAKE, salient_idx=FAKE)
     d.update(kw)
     return B.mes_delta(**d)
 

@@ -42,8 +42,8 @@ def test_pack_unpack_roundtrip(bits, shape):
 
 @pytest.mark.parametrize("bits", [1, 2, 3])
 def test_pack_every_bit_is_used_exactly_once(bits):
-    """One-hot probes: each (row tile, column, code bit) lands on its own bit of the packed words, none
-    collide, and the place is the one the layout specification gives."""
+    """One-hot probes: each (row, column, code bit) lands on its own bit of the packed words, none collide,
+    and the place is the one the layout specification gives."""
     seen = set()
     for row in (5, 21):
         for col in range(128):
@@ -51,23 +51,33 @@ def test_pack_every_bit_is_used_exactly_once(bits):
                 codes = np.zeros((32, 128), dtype=np.uint8)
                 codes[row, col] = 1 << cb
                 packed = O.pack_codes(codes, bits)
-                assert packed.shape == (2, 1, 128 * bits)        # rows are padded to 64
+                assert packed.shape == (1, 4, 64 * bits)         # rows are padded to 64 = four row tiles
                 nz = np.argwhere(packed != 0)
-                assert len(nz) == 1 and nz[0][0] == 0 and nz[0][1] == 0
+                assert len(nz) == 1 and nz[0][0] == 0 and nz[0][1] == row // 16
                 widx = int(nz[0][2])
-                word = int(packed[0, 0, widx])
+                word = int(packed[0, row // 16, widx])
                 assert word & (word - 1) == 0                    # exactly one bit
                 bit = word.bit_length() - 1
                 g, q, p = col // 32, (col % 32) // 8, col % 8
-                lane, rt = 16 * g + row % 16, row // 16
-                if bits == 1 or (bits == 3 and cb == 2):         # one word per (lane, rt), bit 4 p + q
-                    off = 256 if bits == 3 else 0
-                    assert (widx, bit) == (off + 2 * lane + rt, 4 * p + q)
-                else:                                            # two words per (lane, rt), 2-bit fields
-                    assert (widx, bit) == (4 * lane + 2 * rt + q // 2, 4 * p + 2 * (q % 2) + cb)
-                assert (widx, bit) not in seen
-                seen.add((widx, bit))
+                lane = 16 * g + row % 16
+                if bits == 1 or (bits == 3 and cb == 2):         # one word per lane, bit 4 p + q
+                    off = 128 if bits == 3 else 0
+                    assert (widx, bit) == (off + lane, 4 * p + q)
+                else:                                            # two words per lane, 2-bit fields
+                    assert (widx, bit) == (2 * lane + q // 2, 4 * p + 2 * (q % 2) + cb)
+                assert (row // 16, widx, bit) not in seen
+                seen.add((row // 16, widx, bit))
     assert len(seen) == 2 * 128 * bits
+
+
+def test_pack_is_chunk_major():
+    """All row tiles of one 128-column chunk are contiguous: the block of (chunk c, row tile jt) is packed[c, jt]."""
+    codes = np.zeros((64, 384), dtype=np.uint8)
+    codes[40, 300] = 3                                           # row tile 2, chunk 2
+    packed = O.pack_codes(codes, 2)
+    assert packed.shape == (3, 4, 128)
+    nz = np.argwhere(packed != 0)
+    assert len(nz) == 1 and tuple(nz[0][:2]) == (2, 2)
 
 
 def test_packed_words_are_fp4_operands():
@@ -79,18 +89,17 @@ def test_packed_words_are_fp4_operands():
         return (m * 0.5 if e == 0 else (1 + m * 0.5) * 2.0 ** (e - 1)) * (-1 if n & 8 else 1)
     assert [e2m1(u) for u in range(4)] == [0.0, 0.5, 1.0, 1.5]
     assert e2m1(0b0100) == 2.0
-    codes = _rng(9).integers(0, 8, size=(32, 128), dtype=np.uint8)
+    codes = _rng(9).integers(0, 8, size=(16, 128), dtype=np.uint8)
     packed = O.pack_codes(codes, 3)[0, 0]
-    low, high = packed[:256].reshape(64, 2, 2), packed[256:].reshape(64, 2)
+    low, high = packed[:128].reshape(64, 2), packed[128:]
     for lane in (0, 17, 63):
-        for rt in range(2):
-            row, g = 16 * rt + lane % 16, lane // 16
-            for q in range(4):
-                lo_reg = (int(low[lane, rt, q // 2]) >> (2 * (q % 2))) & 0x33333333
-                hi_reg = ((int(high[lane, rt]) << 2) >> q) & 0x44444444
-                for p in range(8):
-                    u = int(codes[row, 32 * g + 8 * q + p])
-                    assert e2m1((lo_reg >> (4 * p)) & 15) + e2m1((hi_reg >> (4 * p)) & 15) == u / 2
+        row, g = lane % 16, lane // 16
+        for q in range(4):
+            lo_reg = (int(low[lane, q // 2]) >> (2 * (q % 2))) & 0x33333333
+            hi_reg = ((int(high[lane]) << 2) >> q) & 0x44444444
+            for p in range(8):
+                u = int(codes[row, 32 * g + 8 * q + p])
+                assert e2m1((lo_reg >> (4 * p)) & 15) + e2m1((hi_reg >> (4 * p)) & 15) == u / 2
 
 
 def test_pack_padding_and_salient_are_zero_codes():
@@ -106,12 +115,16 @@ def test_pack_padding_and_salient_are_zero_codes():
 def test_base_and_salient_tiling_roundtrip_and_slot_rule():
     w = _rng(3).integers(0, 65536, size=(70, 100), dtype=np.uint16)
     t = O.pack_base(w)
-    assert t.shape == (128 // 16, 128 // 32, 64, 8)
+    assert t.shape == (1, 128 // 16, 4, 64, 8)
     assert np.array_equal(O.unpack_base(t, 70, 100), w)
-    # slot rule stated independently: lane = 16 g + r holds W[16 jt + r, 32 kb + 8 g + e]
+    # slot rule stated independently: lane = 16 g + r holds W[16 jt + r, 128 c + 32 kb + 8 g + e]
     for (j, i) in [(0, 0), (17, 45), (69, 99), (33, 8)]:
-        jt, r, kb, g, e = j // 16, j % 16, i // 32, (i % 32) // 8, i % 8
-        assert t[jt, kb, 16 * g + r, e] == w[j, i]
+        jt, r, c, kb, g, e = j // 16, j % 16, i // 128, (i % 128) // 32, (i % 32) // 8, i % 8
+        assert t[c, jt, kb, 16 * g + r, e] == w[j, i]
+    w2 = _rng(5).integers(0, 65536, size=(32, 384), dtype=np.uint16)
+    t2 = O.pack_base(w2)
+    assert t2.shape == (3, 4, 4, 64, 8) and t2[2, 1, 3, 16 * 2 + 5, 7] == w2[21, 256 + 96 + 16 + 7]
+    assert np.array_equal(O.unpack_base(t2, 32, 384), w2)
     s = _rng(4).standard_normal((20, 40)).astype(np.float16)
     ts = O.pack_salient(s)
     assert ts.shape == (4, 2, 64, 8)
