@@ -1,7 +1,9 @@
 // The serving hot path (Eq. 4, batched across experts):
 //   y[t] = x[t] W^T + step_e .* (x_ns[t] (U_e - z)^T) + x_s[t] D_e^T
 // for groups of up to 64 tokens.  Per group: one small preparation launch, the main streaming launch
-// and, only when the columns had to be split over workgroups, a small reduction launch.
+// and, only when the columns had to be split over workgroups, a small reduction launch.  (Letting the last
+// workgroup of a row group do that reduction inside the main kernel was measured and is slower: the device-wide
+// hand-over costs more than the extra launch.)
 //
 // Main kernel.  A workgroup of eight wavefronts (two per SIMD: while one waits for memory or for the
 // matrix core the other issues) owns 128 output channels, one 16-row tile per wavefront, and a range of
@@ -72,14 +74,14 @@ struct LinearParams {
   u32x4* xs;        // workspace: salient activations per visit, fp16, scaled per token  [visit][k_pad/32][64 lanes]
   float* corr;      // workspace: per-token  z * (sum_all x - sum_salient x)  [64]
   float* sal_scale; // workspace: per-token power of two the salient activations were divided by  [64]
-  float* partial;   // workspace: [nsplit][64 tokens][d_out_pad] fp32 (split columns only)
+  f32x4* partial;   // workspace: [row group][nsplit][4 tiles][threads of a workgroup] partial result tiles (split columns only)
   const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
   const char* sal[kMaxSlots];
   const int32_t* sidx[kMaxSlots];
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
   uint8_t tok_slot[kTokGroup];            // slot of every token of the group, 0xFF past the last token
-  uint8_t vis_slot[kMaxVisits + 1], vis_tt[kMaxVisits + 1];   // visits (slot, tile) in tile-major order
+  int vis_info[kMaxVisits + 1];           // visits (slot, tile) in tile-major order: slot | tile << 8
   int tile_first[4], tile_last[4];        // slots that own tokens of 16-token tile tt: tile_first[tt] .. tile_last[tt]
   int d_in, d_out, d_out_pad, n_chunks, n_jt, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
   float z;
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
     // within 2^-29 of that largest one, and no value overflows.  The main kernel multiplies back.
     const int v = b - p.n_chunks;
-    const int a = p.vis_slot[v], tt = p.vis_tt[v];
+    const int a = p.vis_info[v] & 0xff, tt = p.vis_info[v] >> 8;
     const int32_t* si = p.sidx[a];
     __shared__ uint32_t smax[16];
     if (tid < 16) smax[tid] = 0;
@@ -399,14 +401,14 @@ struct Stream {
 
   const LinearParams& p;
   int lane, n, jt;
-  char* park;                 // this wavefront's LDS area: [NA][kSlotLds]
+  char* parkp;                // this wavefront's LDS area: [NA][kSlotLds]
   uint32_t slot_tok[TT];
   int scale[2][TT];           // per-token block scales of the current / next chunk
   u32x4 base[2][4];
   CodeRegs<BITS> code[2][NA];
   f32x4 acc_base[TT], acc_raw[TT];
 
-  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jt_, char* park_) : p(p_), lane(lane_), n(lane_ & 15), jt(jt_), park(park_) {
+  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jt_, char* park_) : p(p_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       slot_tok[tt] = p.tok_slot[16 * tt + n];
@@ -436,14 +438,12 @@ struct Stream {
     for (int a = 0; a < NA; ++a) load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
   }
 
-  // Register buffer BUF -> this wavefront's LDS area, then the buffer is reloaded with chunk `c2` (two chunks
-  // ahead: the other buffer holds the chunk in between, already in flight).
+  // Register buffer BUF (the chunk that starts now) -> this wavefront's LDS area.
   template <int BUF>
-  __device__ __forceinline__ void park_and_reload(int c2) {
-    const size_t off = ((size_t)c2 * p.n_jt + jt) * kSlotLds;
+  __device__ __forceinline__ void park() {
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
-      char* dst = park + a * kSlotLds;
+      char* dst = parkp + a * kSlotLds;
       const CodeRegs<BITS>& r = code[BUF][a];
       if constexpr (BITS == 1) {
         *reinterpret_cast<uint32_t*>(dst + lane * 4) = r.lo[0];
@@ -451,18 +451,32 @@ struct Stream {
         *reinterpret_cast<u32x2*>(dst + lane * 8) = u32x2{r.lo[0], r.lo[1]};
         if constexpr (BITS == 3) *reinterpret_cast<uint32_t*>(dst + 512 + lane * 4) = r.hi;
       }
-      load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
     }
+  }
+
+  // Tile tt's share of the requests of one chunk: code words of chunk c2 (two ahead) into the register buffer
+  // that was just parked, base weights and scales of chunk cn (one ahead) into the other base buffer.
+  template <int BUF>
+  __device__ __forceinline__ void request_share(int tt, int cn, int c2) {
+    const size_t off = ((size_t)c2 * p.n_jt + jt) * kSlotLds;
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+      if (a * TT / NA == tt) load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
+    const char* src = p.w_base + ((size_t)cn * p.n_jt + jt) * 4096 + lane * 16;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+      if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
+    scale[BUF ^ 1][tt] = reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale)[16 * tt + n];
   }
 
   __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
     CodeRegs<BITS> r;
-    load_codes<BITS>(park + a * kSlotLds, lane, r);
+    load_codes<BITS>(parkp + a * kSlotLds, lane, r);
     return r;
   }
 
-  // Loads of one chunk() call that are younger than its stage copy.
-  static constexpr int kYounger = 4 + TT;
+  // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
+  static constexpr int kYounger = NA * (BITS == 3 ? 2 : 1) + 4 + TT;
 
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
   template <int BUF>
@@ -476,19 +490,18 @@ struct Stream {
 #if MES_EXP == 2
     cn = 0; c2 = 0;
 #endif
-    park_and_reload<BUF>(c2);
+    park<BUF>();
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
-    load_base<BUF ^ 1>(cn);
-    load_scales<BUF ^ 1>(cn);
     MES_CSTAMP(3);
 #if MES_EXP == 3
-    // loads only: keep the loaded registers alive without any arithmetic
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) asm volatile("" : : "v"(base[BUF][kb]));
     if (false)
 #endif
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
+      // this tile's share of the next chunks' requests: spreading them over the chunk keeps the memory
+      // pipeline fed without ever asking it to take a whole chunk's loads at once (which blocks the
+      // wavefront, and with it the arithmetic it could be doing, until the pipeline has room)
+      request_share<BUF>(tt, cn, c2);
       const v8i bhi = lds_fp8(cur, tt, 0, lane), blo = lds_fp8(cur, tt, 1, lane);
       const int first = p.tile_first[tt], last = p.tile_last[tt];
       CodeRegs<BITS> cr = parked(first);
@@ -556,51 +569,50 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   ws.template load_code_regs<0>(chunk_at(0));
   ws.template load_code_regs<1>(chunk_at(1));
 
-  // what the epilogue needs from memory, requested early: the owning expert's step per output channel
-  // and the zero-point correction per token
-  f32x4 stepv[TT];
-  float corr[TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) {
-    const int tl = 16 * tt + n;
-    const uint32_t at = slot_tok[tt];
-    corr[tt] = sp == 0 ? p.corr[tl] : 0.0f;   // belongs to the whole column range: only the first split applies it
-    const int j = 16 * jt + 4 * g;
-    stepv[tt] = f32x4{0, 0, 0, 0};
-    if (at != 0xffu && j < p.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(p.step[at] + j);
-  }
-
-  // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits, four pairs
+  // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits, eight pairs
   // of loads in flight.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
   MES_STAMP(12);
   f32x4 acc_sal[TT];
+  float sal_scale[TT];
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt) acc_sal[tt] = f32x4{0, 0, 0, 0};
+  for (int tt = 0; tt < TT; ++tt) { acc_sal[tt] = f32x4{0, 0, 0, 0}; sal_scale[tt] = p.sal_scale[16 * tt + n]; }
+  // What the epilogue needs from memory -- the owning expert's step per output channel and the zero-point
+  // correction per token -- sits behind a pointer that depends on the token's slot.  The pointers are
+  // fetched here, the values after the wait at the end of this start-up phase; they arrive while the
+  // chunks stream.
+  const float* step_ptr[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) step_ptr[tt] = slot_tok[tt] != 0xffu ? p.step[slot_tok[tt]] : nullptr;
   if (p.k > 0) {
-    constexpr int SD = 4;
+    constexpr int SD = 8;
     const int n_pairs = p.n_vis * p.n_sb;
     const int mine = (n_pairs - sp + p.nsplit - 1) / p.nsplit;   // pairs sp, sp + nsplit, ...
     u32x4 sx[SD], sd[SD];
-    auto load_pair = [&](int i, u32x4& x, u32x4& d) {
-      const int pair = sp + (i < mine ? i : mine - 1) * p.nsplit;
-      const int v = pair / p.n_sb, sb = pair - v * p.n_sb;
-      const int a = p.vis_slot[v];
-      x = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)v * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
-      d = ld128(p.sal[a] + ((size_t)jt * p.n_sb + sb) * 1024, (uint32_t)lane * 16u);
+    int stt[SD];
+    // (visit, block) of the next pair to request, advanced without divisions
+    int rv = 0, rsb = sp, rleft = mine;
+    while (rsb >= p.n_sb) { rsb -= p.n_sb; ++rv; }
+    auto request = [&](u32x4& x, u32x4& d, int& tt_out) {
+      const int info = p.vis_info[rv];
+      tt_out = rleft > 0 ? info >> 8 : -1;
+      x = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)rv * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
+      d = ld128(p.sal[info & 0xff] + ((size_t)jt * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
+      if (rleft > 1) {   // past the last pair the same (valid) pair is requested again and ignored
+        rsb += p.nsplit;
+        while (rsb >= p.n_sb) { rsb -= p.n_sb; ++rv; }
+      }
+      --rleft;
     };
     if (mine > 0) {
 #pragma unroll
-      for (int i = 0; i < SD; ++i) load_pair(i, sx[i], sd[i]);
+      for (int i = 0; i < SD; ++i) request(sx[i], sd[i], stt[i]);
       for (int i0 = 0; i0 < mine; i0 += SD) {
 #pragma unroll
         for (int i = 0; i < SD; ++i) {
-          if (i0 + i < mine) {
-            const int tt_dyn = p.vis_tt[(sp + (i0 + i) * p.nsplit) / p.n_sb];
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt)
-              if (tt == tt_dyn) acc_sal[tt] = mfma_f16(sd[i], sx[i], acc_sal[tt]);
-          }
-          load_pair(i0 + i + SD, sx[i], sd[i]);
+          for (int tt = 0; tt < TT; ++tt)
+            if (tt == stt[i]) acc_sal[tt] = mfma_f16(sd[i], sx[i], acc_sal[tt]);
+          request(sx[i], sd[i], stt[i]);
         }
       }
     }
@@ -608,9 +620,18 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   MES_STAMP(13);
   // the salient product starts the base accumulators (the scale is an exact power of two)
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt) acc_base[tt] = acc_sal[tt] * p.sal_scale[16 * tt + n];
+  for (int tt = 0; tt < TT; ++tt) acc_base[tt] = acc_sal[tt] * sal_scale[tt];
 
   stage_barrier<0>();
+  f32x4 stepv[TT];
+  float corr[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt) {
+    const int j = 16 * jt + 4 * g;
+    corr[tt] = sp == 0 ? p.corr[16 * tt + n] : 0.0f;   // belongs to the whole column range: only the first split applies it
+    stepv[tt] = f32x4{0, 0, 0, 0};
+    if (step_ptr[tt] != nullptr && j < p.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(step_ptr[tt] + j);
+  }
   MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
     ws.template chunk<0>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
@@ -622,41 +643,53 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // The last matrix instructions above were issued from an assembly block: give them the wait states a
   // matrix result needs before vector instructions may read it.
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  f32x4 o[TT];
+#pragma unroll
+  for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) o[tt][v] = acc_base[tt][v] + stepv[tt][v] * (acc_raw[tt][v] - corr[tt]);
+
+  if (p.nsplit > 1) {
+    // Split columns: the partial tile goes to the workspace in this kernel's own thread order (fully
+    // coalesced); the reduction launch adds the tiles of a row group in split order.
+    constexpr int NT = 64 * NW;
+    f32x4* part = p.partial + ((size_t)rg * p.nsplit + sp) * (4 * NT);
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) part[tt * NT + tid] = o[tt];
+    return;
+  }
   if (!live) return;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
-    const int tl = 16 * tt + n, t = p.t0 + tl;
-    const int j = 16 * jt + 4 * g;
-    f32x4 o;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) o[v] = acc_base[tt][v] + stepv[tt][v] * (acc_raw[tt][v] - corr[tt]);
-    if (p.nsplit == 1) {
-      if (t < p.T && j < p.d_out) {
-        uint2 pk;
-        pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
-        pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-        *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
-      }
-    } else {
-      *reinterpret_cast<f32x4*>(p.partial + ((size_t)(sp * kTokGroup + tl) * p.d_out_pad + j)) = o;
+    const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
+    if (t < p.T && j < p.d_out) {
+      uint2 pk;
+      pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
+      pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
+      *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
     }
   }
   MES_STAMP(14);
 }
 
-// Split columns only: y = sum over splits (in split order) of the fp32 partial tiles, rounded to bf16.
-__global__ __launch_bounds__(256) void k_reduce_splits(const LinearParams p, int n_tok) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;
-  const int quads = p.d_out / 4;
-  if (idx >= n_tok * quads) return;
-  const int tl = idx / quads, j = (idx - tl * quads) * 4;
+// Split columns only: y = sum over splits (in split order) of the fp32 partial tiles, rounded to bf16.  One
+// workgroup per (row group, token tile), threads laid out as in the main kernel.
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p) {
+  constexpr int NT = 64 * NW;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
+  const int rg = blockIdx.x, tt = blockIdx.y;
+  const f32x4* part = p.partial + (size_t)rg * p.nsplit * (4 * NT) + tt * NT + tid;
   f32x4 o = {0, 0, 0, 0};
-  for (int s = 0; s < p.nsplit; ++s)
-    o += *reinterpret_cast<const f32x4*>(p.partial + ((size_t)(s * kTokGroup + tl) * p.d_out_pad + j));
-  uint2 pk;
-  pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
-  pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-  *reinterpret_cast<uint2*>(p.y + (size_t)(p.t0 + tl) * p.d_out + j) = pk;
+  for (int s = 0; s < p.nsplit; ++s) o += part[(size_t)s * (4 * NT)];
+  const int jt = rg * NW + wave;
+  const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
+  if (jt < p.n_jt && t < p.T && j < p.d_out) {
+    uint2 pk;
+    pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
+    pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
+    *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
+  }
 }
 
 // Active experts one launch handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
@@ -704,7 +737,8 @@ WorkspaceLayout workspace_layout(int d_in, int d_out) {
   w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes + 1024;   // the copy of the last stage's partial block reads a full KiB
   w.xs = off;      off += (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
   w.corr = off;    off += 512;   // corrections, then salient scales
-  w.partial = off; off += pl.nsplit > 1 ? (size_t)pl.nsplit * kTokGroup * po * sizeof(float) : 0;
+  const size_t rgs = (size_t)(po / 16 + kWaves - 1) / kWaves;
+  w.partial = off; off += pl.nsplit > 1 ? rgs * pl.nsplit * 4 * (64 * kWaves) * 16 : 0;
   w.total = off;
   return w;
 }
@@ -755,7 +789,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.xs = reinterpret_cast<u32x4*>(ws + wl.xs);
   p.corr = reinterpret_cast<float*>(ws + wl.corr);
   p.sal_scale = p.corr + kTokGroup;
-  p.partial = reinterpret_cast<float*>(ws + wl.partial);
+  p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
   const int po = ceil_to(d0.d_out, kRowPad), pi = ceil_to(d0.d_in, kColPad);
   p.d_in = d0.d_in;
   p.d_out = d0.d_out;
@@ -811,11 +845,10 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
         const int l = p.lo[a] > 16 * t ? p.lo[a] : 16 * t;
         const int h = p.hi[a] < 16 * t + 16 ? p.hi[a] : 16 * t + 16;
         if (h <= l) continue;
-        p.vis_slot[nv] = (uint8_t)a;
-        p.vis_tt[nv] = (uint8_t)t;
+        p.vis_info[nv] = a | (t << 8);
         ++nv;
       }
-    for (int v = nv; v <= kMaxVisits; ++v) { p.vis_slot[v] = 0; p.vis_tt[v] = 0; }
+    for (int v = nv; v <= kMaxVisits; ++v) p.vis_info[v] = 0;
     for (int t = 0; t < 4; ++t) {
       p.tile_first[t] = 0; p.tile_last[t] = 0;
       const int tl0 = 16 * t, tl1 = 16 * t + 15 < nt - 1 ? 16 * t + 15 : nt - 1;
@@ -834,8 +867,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     }
     if (e != hipSuccess) return e;
     if (pl.nsplit > 1) {
-      const int total = nt * (d0.d_out / 4);
-      k_reduce_splits<<<(total + 255) / 256, 256, 0, s>>>(p, nt);
+      k_reduce_splits<kWaves><<<dim3(grid.x, tt), 64 * kWaves, 0, s>>>(p);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     t0 += nt;
