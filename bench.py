@@ -4,7 +4,9 @@
 Workload (config "c4", the one the headline metric is quoted on): the seven linear shapes of one
 Mistral-7B block, 16 experts resident, a decode batch of 64 tokens routed Zipf(1.1), 2-bit
 non-salient codes, 64 fp16 salient input channels.  One "step" = one pass of that batch through
-all seven linears (seven mes_delta_linear calls).  A token = one row of x through all seven.
+all seven linears: four library calls, because layers that read the same activations share one
+(mes_delta_linear_multi): [q, k, v], [o], [gate, up], [down].  `--unfused` issues seven single calls.
+A token = one row of x through all seven.
 
 Prints ONE JSON line.  `value` is tokens/s with every input already resident in HBM.
 `roofline` prices the hot kernel against the HBM peak with ALGORITHMIC bytes; `cpu_baseline`
@@ -42,7 +44,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c4", "c2"])
     ap.add_argument("--bits", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--breakdown", action="store_true", help="also time every linear on its own (stderr)")
+    ap.add_argument("--breakdown", action="store_true", help="also time every call on its own (stderr)")
+    ap.add_argument("--unfused", action="store_true", help="seven single-layer calls per step instead of four")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; --gpus must be 1 (nothing here uses a second GPU).", file=sys.stderr)
@@ -94,15 +97,33 @@ def main():
                                 bits=wl.bits, d_out=wl.d_out))
         del wl
     torch.cuda.synchronize()
-    calls_per_step = 7 if args.workload == "c4" else 1
+    # ---------------------------------------------------------------- the calls of one step
+    if args.workload == "c4" and not args.unfused:
+        groups = [[0, 1, 2], [3], [4, 5], [6]]          # layers that read the same activations share a call
+    else:
+        groups = [[i] for i in range(len(layers))]
+    calls = []
+    for g_ in groups:
+        Ls = [layers[i] for i in g_]
+        if len(Ls) == 1:
+            L = Ls[0]
+            calls.append(dict(name=L["name"], bytes=L["bytes"],
+                              run=(lambda L=L: L["lin"](L["x"], L["seg"], L["y"]))))
+        else:
+            fused = mes.DeltaLinearMulti([(L["lin"].w, L["lin"].experts) for L in Ls], T)
+            ys = [L["y"] for L in Ls]
+            # the shared activations are read (and credited) once
+            nbytes = sum(L["bytes"] for L in Ls) - (len(Ls) - 1) * 2 * T * Ls[0]["d_in"]
+            calls.append(dict(name="+".join(L["name"] for L in Ls), bytes=nbytes,
+                              run=(lambda fused=fused, L0=Ls[0], ys=ys: fused(L0["x"], L0["seg"], ys))))
+    calls_per_step = len(calls) if args.workload == "c4" else 1
 
     def one_step(i):
         if args.workload == "c4":
-            for L in layers:
-                L["lin"](L["x"], L["seg"], L["y"])
+            for c in calls:
+                c["run"]()
         else:
-            L = layers[i % copies]
-            L["lin"](L["x"], L["seg"], L["y"])
+            calls[i % copies]["run"]()
 
     # ---------------------------------------------------------------- timed region
     for i in range(args.warmup):
@@ -120,10 +141,22 @@ def main():
     ms_per_step = ms_total / args.steps
     tokens_per_s = T * args.steps / (ms_total * 1e-3)
 
-    step_bytes = sum(L["bytes"] for L in layers) if args.workload == "c4" else layers[0]["bytes"]
+    # ---------------------------------------------------------------- roofline of the dominant kernel
+    # The library records HIP events on the call's own stream right around its streaming kernel
+    # (k_delta_linear); the same step sequence is replayed so that the caches are in the same state.
+    timer = mes.KernelTimer()
+    reps = max(10, min(50, args.steps))
+    kernel_us = [0.0] * len(calls)
+    for r in range(reps):
+        for ci, c in enumerate(calls if args.workload == "c4" else [calls[r % copies]]):
+            timer.arm()
+            c["run"]()
+            kernel_us[ci if args.workload == "c4" else 0] += timer.elapsed_us()
+    n_launches = reps * calls_per_step
+    step_bytes = sum(c["bytes"] for c in calls) if args.workload == "c4" else calls[0]["bytes"]
     launch_bytes = step_bytes / calls_per_step
-    launch_ms = ms_per_step / calls_per_step
-    achieved = launch_bytes / (launch_ms * 1e-3) / 1e9
+    launch_us = sum(kernel_us) / n_launches
+    achieved = launch_bytes / (launch_us * 1e-6) / 1e9
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -135,24 +168,8 @@ def main():
 
     breakdown = None
     if args.breakdown and args.workload == "c4":
-        breakdown = {}
-        for L in layers:
-            for _ in range(5):
-                L["lin"](L["x"], L["seg"], L["y"])
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            # interleave with a big other matrix so this one is not served from the Infinity Cache
-            other = layers[4] if L is not layers[4] else layers[5]
-            reps, tot = 20, 0.0
-            for _ in range(reps):
-                other["lin"](other["x"], other["seg"], other["y"])
-                a.record()
-                L["lin"](L["x"], L["seg"], L["y"])
-                b.record()
-                torch.cuda.synchronize()
-                tot += a.elapsed_time(b)
-            us = tot / reps * 1e3
-            breakdown[L["name"]] = dict(us=round(us, 2), GBs=round(L["bytes"] / us / 1e3, 1), MB=round(L["bytes"] / 1e6, 2))
+        breakdown = {c["name"]: dict(kernel_us=round(kernel_us[ci] / reps, 2), MB=round(c["bytes"] / 1e6, 2),
+                                     GBs=round(c["bytes"] / (kernel_us[ci] / reps) / 1e3, 1)) for ci, c in enumerate(calls)}
         print("breakdown:", json.dumps(breakdown), file=sys.stderr)
 
     # ---------------------------------------------------------------- oracle leg (baseline only)
@@ -207,12 +224,13 @@ def main():
                                "c2: Mistral-7B q_proj 4096x4096, 3 experts, 48 decode tokens 16/16/16, 2-bit, 64 salient; "
                                f"{copies} rotating copies",
                    "tokens": T, "experts": 16 if args.workload == "c4" else 3, "bits": args.bits,
-                   "calls_per_step": calls_per_step,
+                   "calls_per_step": calls_per_step, "fused_calls": [c["name"] for c in calls] if args.workload == "c4" else None,
                    "active_experts": layers[0]["n_active"]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": "k_delta_linear", "algorithmic_bytes_per_launch": int(launch_bytes),
-                     "avg_launch_us": round(launch_ms * 1e3, 3)},
+                     "avg_launch_us": round(launch_us, 3), "launches_timed": n_launches,
+                     "whole_call_GBs": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1)},
         "cpu_baseline": cpu_baseline,
         "parity_rel_fro_vs_oracle_sample": None if parity is None else float(f"{parity:.3e}"),
         "host_wall_ms_per_step": round(t_wall / args.steps * 1e3, 5),

@@ -79,6 +79,7 @@ enum { MES_GRID_SYM = 0, MES_GRID_EQ1 = 1 };
 enum { MES_STEP_GIVEN = 0, MES_STEP_MAXABS = 1, MES_STEP_MEANABS = 2 };
 
 #define MES_MAX_EXPERTS 64
+#define MES_MAX_FUSED 3        /* linear layers one mes_delta_linear_multi call may serve */
 #define MES_LAYOUT_VERSION 3
 
 /* One expert's compressed delta for one linear layer (all pointers DEVICE, caller-owned). */
@@ -90,6 +91,13 @@ typedef struct {
   const int32_t* salient_idx; /* [k] strictly ascending, 0 <= idx < d_in (may be NULL if k = 0) */
 } mes_delta;
 
+/* One linear layer of a mes_delta_linear_multi call (HOST struct; pointers as commented). */
+typedef struct {
+  const void* w_base_tiled;   /* DEVICE: output of mes_pack_base for this layer's [d_out, d_in]        */
+  const mes_delta* experts;   /* HOST array [n_experts]; descriptor pointers are DEVICE                */
+  void* y;                    /* DEVICE: bf16 [T, d_out] row-major, fully overwritten                  */
+} mes_linear;
+
 /* ---- sizes (pure host arithmetic; 0 on invalid arguments) ------------------------------------ */
 size_t mes_base_bytes(int d_in, int d_out);              /* tiled bf16 base                     */
 size_t mes_codes_bytes(int d_in, int d_out, int bits);   /* packed low-bit codes of one expert  */
@@ -97,6 +105,7 @@ size_t mes_salient_bytes(int d_out, int k);              /* tiled fp16 salient c
 size_t mes_pack_workspace_bytes(void);
 size_t mes_select_workspace_bytes(int n, int d_in, int d_out);
 size_t mes_linear_workspace_bytes(int d_in, int d_out, int max_tokens);
+size_t mes_linear_multi_workspace_bytes(int d_in, const int32_t* d_out /*HOST [n_linears]*/, int n_linears, int max_tokens);
 const char* mes_last_error(void);
 int mes_layout_version(void);
 
@@ -154,6 +163,25 @@ mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* str
 mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, int n_experts,
                             const void* x, int T, const int32_t* seg_offsets, void* y,
                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same hot path for several linear layers that read the SAME activations and routing (Eq. 4 applied to
+ * each layer; e.g. the query / key / value projections, or the gate / up projections, of one block): one
+ * preparation of x and one streaming launch serve all of them, y_l[t] = x[t] (W_l + Delta~_{l,e})^T.
+ * linears: HOST array [n_linears], 1 <= n_linears <= MES_MAX_FUSED.  Every layer has its own base, its own
+ * n_experts expert deltas (with their own salient channels) and its own output; d_out may differ between
+ * layers, d_in, k, bits and grid must be the same for all layers and experts.
+ * x, T, seg_offsets, stream, T = 0: as for mes_delta_linear.
+ * workspace: >= mes_linear_multi_workspace_bytes(d_in, d_out[], n_linears, T), initialised by mes_workspace_init.
+ * With n_linears = 1 this is mes_delta_linear. */
+mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
+                                  const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Measurement hook (for benchmarks; Section 5.4's latency figures time the layer, this times its dominant
+ * kernel): the NEXT mes_delta_linear / mes_delta_linear_multi call of the calling thread records `start_event`
+ * on its stream immediately before its streaming kernel and `stop_event` immediately after it (hipEvent_t
+ * passed as void*, HOST handles owned by the caller; with more than one token group the last group's).
+ * One-shot; two NULLs cancel. */
+mes_status mes_time_next_call(void* start_event, void* stop_event);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,8 @@ STATUS_NAMES = {0: "MES_OK", 1: "MES_ERR_NULL", 2: "MES_ERR_SHAPE", 3: "MES_ERR_
 EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_workspace_bytes",
            "mes_select_workspace_bytes", "mes_linear_workspace_bytes", "mes_last_error", "mes_layout_version",
            "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
-           "mes_workspace_init", "mes_delta_linear"]
+           "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
+           "mes_delta_linear_multi", "mes_time_next_call"]
 
 
 class MesError(RuntimeError):
@@ -41,6 +42,10 @@ class mes_delta(ctypes.Structure):
                 ("bits", ctypes.c_int32), ("grid", ctypes.c_int32), ("layout_version", ctypes.c_int32),
                 ("codes", ctypes.c_void_p), ("step", ctypes.c_void_p), ("salient", ctypes.c_void_p),
                 ("salient_idx", ctypes.c_void_p)]
+
+
+class mes_linear(ctypes.Structure):
+    _fields_ = [("w_base_tiled", ctypes.c_void_p), ("experts", ctypes.POINTER(mes_delta)), ("y", ctypes.c_void_p)]
 
 
 def _load() -> ctypes.CDLL:
@@ -79,6 +84,13 @@ def _load() -> ctypes.CDLL:
     lib.mes_delta_linear.restype = c_int
     lib.mes_delta_linear.argtypes = [vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
                                      ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
+    lib.mes_linear_multi_workspace_bytes.restype = c_sz
+    lib.mes_linear_multi_workspace_bytes.argtypes = [c_int, ctypes.POINTER(ctypes.c_int32), c_int, c_int]
+    lib.mes_delta_linear_multi.restype = c_int
+    lib.mes_delta_linear_multi.argtypes = [ctypes.POINTER(mes_linear), c_int, c_int, vp, c_int,
+                                           ctypes.POINTER(ctypes.c_int32), vp, c_sz, vp]
+    lib.mes_time_next_call.restype = c_int
+    lib.mes_time_next_call.argtypes = [vp, vp]
     return lib
 
 
@@ -215,3 +227,58 @@ class DeltaLinear:
 
 def mes_delta_linear(w_base_tiled, experts, x, seg_offsets, y=None, workspace=None):
     return DeltaLinear(w_base_tiled, experts, x.shape[0], workspace)(x, seg_offsets, y)
+
+
+class DeltaLinearMulti:
+    """Marshalled arguments of mes_delta_linear_multi: several layers that read the same activations and routing."""
+
+    def __init__(self, layers: Sequence, max_tokens: int = 64):
+        """layers: sequence of (w_base_tiled, [PackedDelta per expert])."""
+        self.ws_tiled = [w for w, _ in layers]
+        self.experts = [list(ex) for _, ex in layers]
+        self.n = len(layers)
+        self.E = len(self.experts[0])
+        self.d_in = self.experts[0][0].d_in
+        self.d_out = [ex[0].d_out for ex in self.experts]
+        self.desc = [(mes_delta * self.E)(*[e.descriptor() for e in ex]) for ex in self.experts]
+        dev = self.ws_tiled[0].device
+        d = (ctypes.c_int32 * self.n)(*self.d_out)
+        nbytes = max(lib.mes_linear_multi_workspace_bytes(self.d_in, d, self.n, max_tokens), 16)
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        _check(lib.mes_workspace_init(_ptr(self.ws), nbytes, _stream(dev)))
+
+    def __call__(self, x: torch.Tensor, seg_offsets: Sequence[int], ys: Optional[Sequence[torch.Tensor]] = None):
+        T = x.shape[0]
+        if ys is None:
+            ys = [torch.empty((T, d), dtype=torch.bfloat16, device=x.device) for d in self.d_out]
+        lin = (mes_linear * self.n)(*[mes_linear(self.ws_tiled[l].data_ptr(), self.desc[l], ys[l].data_ptr())
+                                      for l in range(self.n)])
+        seg = (ctypes.c_int32 * (self.E + 1))(*seg_offsets)
+        _check(lib.mes_delta_linear_multi(lin, self.n, self.E, _ptr(x), T, seg, _ptr(self.ws), self.ws.numel(),
+                                          _stream(x.device)))
+        return list(ys)
+
+
+class KernelTimer:
+    """HIP events recorded by the library around its streaming kernel (mes_time_next_call)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.start, self.stop = ctypes.c_void_p(), ctypes.c_void_p()
+        for ev in (self.start, self.stop):
+            if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+
+    def arm(self) -> None:
+        _check(lib.mes_time_next_call(self.start, self.stop))
+
+    def elapsed_us(self) -> float:
+        if self.hip.hipEventSynchronize(self.stop) != 0:
+            raise RuntimeError("hipEventSynchronize failed")
+        ms = ctypes.c_float()
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), self.start, self.stop) != 0:
+            raise RuntimeError("hipEventElapsedTime failed")
+        return ms.value * 1e3

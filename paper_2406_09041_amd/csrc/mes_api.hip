@@ -7,6 +7,7 @@
 namespace mes {
 
 static thread_local char g_err[512] = "";
+static thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 mes_status fail(mes_status st, const char* fmt, ...) {
   va_list ap;
@@ -71,9 +72,19 @@ size_t mes_select_workspace_bytes(int n, int d_in, int d_out) {
   return (size_t)ceil_to(d_in, 32) * 8 + (size_t)ceil_to(d_out, 64) * 4 + (size_t)ceil_to(d_in, 32) * 4;
 }
 
+size_t mes_linear_multi_workspace_bytes(int d_in, const int32_t* d_out, int n_linears, int max_tokens) {
+  if (d_in <= 0 || !d_out || n_linears < 1 || n_linears > MES_MAX_FUSED || max_tokens < 0) return 0;
+  int d[MES_MAX_FUSED];
+  for (int l = 0; l < n_linears; ++l) {
+    if (d_out[l] <= 0) return 0;
+    d[l] = d_out[l];
+  }
+  return linear_workspace_bytes(d_in, d, n_linears, max_tokens);
+}
+
 size_t mes_linear_workspace_bytes(int d_in, int d_out, int max_tokens) {
-  if (d_in <= 0 || d_out <= 0 || max_tokens < 0) return 0;
-  return linear_workspace_bytes(d_in, d_out, max_tokens);
+  const int32_t d = d_out;
+  return mes_linear_multi_workspace_bytes(d_in, &d, 1, max_tokens);
 }
 
 mes_status mes_pack_base(const void* w, int d_in, int d_out, void* w_tiled_out, void* stream) {
@@ -158,34 +169,59 @@ mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* str
   return check_hip(launch_fill_zero(workspace, workspace_bytes, (hipStream_t)stream), "mes_workspace_init");
 }
 
+mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
+                                  const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream) {
+  const char* who = "mes_delta_linear";
+  if (n_linears < 1 || n_linears > MES_MAX_FUSED)
+    return fail(MES_ERR_SHAPE, "%s: n_linears = %d outside [1, %d]", who, n_linears, MES_MAX_FUSED);
+  if (n_experts < 1 || n_experts > MES_MAX_EXPERTS)
+    return fail(MES_ERR_SHAPE, "%s: n_experts = %d outside [1, %d]", who, n_experts, MES_MAX_EXPERTS);
+  if (T < 0) return fail(MES_ERR_SHAPE, "%s: T = %d is negative", who, T);
+  if (!linears || !seg_offsets) return fail(MES_ERR_NULL, "%s: linears / seg_offsets is null", who);
+  int32_t d_outs[MES_MAX_FUSED];
+  for (int l = 0; l < n_linears; ++l) {
+    if (!linears[l].experts) return fail(MES_ERR_NULL, "%s: experts is null", who);
+    for (int e = 0; e < n_experts; ++e) {
+      if (mes_status st = check_delta(&linears[l].experts[e], who)) return st;
+      const mes_delta &a = linears[0].experts[0], &b = linears[l].experts[e];
+      if (a.d_in != b.d_in || a.k != b.k || a.bits != b.bits || a.grid != b.grid || b.d_out != linears[l].experts[0].d_out)
+        return fail(MES_ERR_SHAPE, "%s: expert %d of layer %d differs in d_in/d_out/k/bits/grid", who, e, l);
+    }
+    d_outs[l] = linears[l].experts[0].d_out;
+  }
+  if (seg_offsets[0] != 0) return fail(MES_ERR_SEGMENTS, "%s: seg_offsets[0] must be 0 (got %d)", who, seg_offsets[0]);
+  for (int e = 0; e < n_experts; ++e)
+    if (seg_offsets[e + 1] < seg_offsets[e]) return fail(MES_ERR_SEGMENTS, "%s: seg_offsets decreases at %d", who, e + 1);
+  if (seg_offsets[n_experts] != T)
+    return fail(MES_ERR_SEGMENTS, "%s: seg_offsets[%d] = %d, expected T = %d", who, n_experts, seg_offsets[n_experts], T);
+  if (T == 0) return MES_OK;
+  if (!x) return fail(MES_ERR_NULL, "%s: w_base / x / y is null", who);
+  for (int l = 0; l < n_linears; ++l) {
+    if (!linears[l].w_base_tiled || !linears[l].y) return fail(MES_ERR_NULL, "%s: w_base / x / y is null", who);
+    if (!aligned16(linears[l].w_base_tiled) || !aligned16(linears[l].y))
+      return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
+  }
+  if (!aligned16(x)) return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
+  const size_t need = mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, T);
+  if (!workspace || workspace_bytes < need) return fail(MES_ERR_WORKSPACE, "%s: workspace needs %zu bytes", who, need);
+  if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "%s: workspace must be 16-byte aligned", who);
+  LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, g_ev_start, g_ev_stop};
+  g_ev_start = g_ev_stop = nullptr;
+  return check_hip(launch_delta_linear(c, (hipStream_t)stream), who);
+}
+
 mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, int n_experts, const void* x, int T,
                             const int32_t* seg_offsets, void* y, void* workspace, size_t workspace_bytes,
                             void* stream) {
-  if (n_experts < 1 || n_experts > MES_MAX_EXPERTS)
-    return fail(MES_ERR_SHAPE, "mes_delta_linear: n_experts = %d outside [1, %d]", n_experts, MES_MAX_EXPERTS);
-  if (T < 0) return fail(MES_ERR_SHAPE, "mes_delta_linear: T = %d is negative", T);
-  if (!experts || !seg_offsets) return fail(MES_ERR_NULL, "mes_delta_linear: experts / seg_offsets is null");
-  for (int e = 0; e < n_experts; ++e) {
-    if (mes_status st = check_delta(&experts[e], "mes_delta_linear")) return st;
-    const mes_delta &a = experts[0], &b = experts[e];
-    if (a.d_in != b.d_in || a.d_out != b.d_out || a.k != b.k || a.bits != b.bits || a.grid != b.grid)
-      return fail(MES_ERR_SHAPE, "mes_delta_linear: expert %d differs from expert 0 in d_in/d_out/k/bits/grid", e);
-  }
-  if (seg_offsets[0] != 0) return fail(MES_ERR_SEGMENTS, "mes_delta_linear: seg_offsets[0] must be 0 (got %d)", seg_offsets[0]);
-  for (int e = 0; e < n_experts; ++e)
-    if (seg_offsets[e + 1] < seg_offsets[e])
-      return fail(MES_ERR_SEGMENTS, "mes_delta_linear: seg_offsets decreases at %d", e + 1);
-  if (seg_offsets[n_experts] != T)
-    return fail(MES_ERR_SEGMENTS, "mes_delta_linear: seg_offsets[%d] = %d, expected T = %d", n_experts, seg_offsets[n_experts], T);
-  if (T == 0) return MES_OK;
-  if (!w_base_tiled || !x || !y) return fail(MES_ERR_NULL, "mes_delta_linear: w_base / x / y is null");
-  if (!aligned16(w_base_tiled) || !aligned16(x) || !aligned16(y))
-    return fail(MES_ERR_ALIGN, "mes_delta_linear: w_base, x and y must be 16-byte aligned");
-  const size_t need = mes_linear_workspace_bytes(experts[0].d_in, experts[0].d_out, T);
-  if (!workspace || workspace_bytes < need) return fail(MES_ERR_WORKSPACE, "mes_delta_linear: workspace needs %zu bytes", need);
-  if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "mes_delta_linear: workspace must be 16-byte aligned");
-  LinearCall c{w_base_tiled, experts, n_experts, x, T, seg_offsets, y, workspace, workspace_bytes};
-  return check_hip(launch_delta_linear(c, (hipStream_t)stream), "mes_delta_linear");
+  const mes_linear one{w_base_tiled, experts, y};
+  return mes_delta_linear_multi(&one, 1, n_experts, x, T, seg_offsets, workspace, workspace_bytes, stream);
+}
+
+mes_status mes_time_next_call(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return fail(MES_ERR_NULL, "mes_time_next_call: give both events or neither");
+  g_ev_start = (hipEvent_t)start_event;
+  g_ev_stop = (hipEvent_t)stop_event;
+  return MES_OK;
 }
 
 }  // extern "C"

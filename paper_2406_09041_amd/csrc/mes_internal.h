@@ -33,17 +33,17 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // ---- launcher implemented in mes_linear.hip -----------------------------------------------------
 struct LinearCall {
-  const void* w_base;
-  const mes_delta* experts;
+  const mes_linear* lin;   // n_linears entries
+  int n_linears;
   int n_experts;
   const void* x;
   int T;
   const int32_t* seg;
-  void* y;
   void* ws;
   size_t ws_bytes;
+  hipEvent_t ev_start, ev_stop;   // measurement hook (nullptr: none)
 };
-size_t linear_workspace_bytes(int d_in, int d_out, int max_tokens);
+size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens);
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
 
 }  // namespace mes

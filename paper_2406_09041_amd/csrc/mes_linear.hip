@@ -65,30 +65,47 @@ constexpr int kStageLds = kStageBlocks * 1024;  // LDS bytes of one stage
 constexpr int kMaxSlots = 16;                   // experts with tokens in one token group (the host cuts groups accordingly)
 constexpr int kMaxVisits = kMaxSlots + 3;       // (expert, 16-token tile) pairs in one group
 
-// Kernel arguments.  Per-expert arrays are indexed by slot.
-struct LinearParams {
+constexpr int kMaxLinears = MES_MAX_FUSED;    // linear layers one launch serves (they read the same activations)
+
+// Per linear layer: where its weights, outputs and its share of the workspace are.  Per-expert arrays are indexed by slot.
+struct PerLinear {
   const char* w_base;
-  const uint16_t* x;
   uint16_t* y;
-  char* xt;         // workspace: one stage per chunk (see k_prepare)
   u32x4* xs;        // workspace: salient activations per visit, fp16, scaled per token  [visit][k_pad/32][64 lanes]
   float* corr;      // workspace: per-token  z * (sum_all x - sum_salient x)  [64]
   float* sal_scale; // workspace: per-token power of two the salient activations were divided by  [64]
-  f32x4* partial;   // workspace: [row group][nsplit][4 tiles][threads of a workgroup] partial result tiles (split columns only)
   const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
   const char* sal[kMaxSlots];
   const int32_t* sidx[kMaxSlots];
+  int d_out, n_jt;
+  int rg_begin, rg_end;   // its row groups among the launch's
+};
+
+// Kernel arguments.
+struct LinearParams {
+  const uint16_t* x;
+  char* xt;         // workspace: one stage per chunk (see k_prepare), shared by the linears
+  f32x4* partial;   // workspace: [row group][nsplit][4 tiles][threads of a workgroup] partial result tiles (split columns only)
+  PerLinear lin[kMaxLinears];
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
   uint8_t tok_slot[kTokGroup];            // slot of every token of the group, 0xFF past the last token
   int vis_info[kMaxVisits + 1];           // visits (slot, tile) in tile-major order: slot | tile << 8
   int tile_first[4], tile_last[4];        // slots that own tokens of 16-token tile tt: tile_first[tt] .. tile_last[tt]
-  int d_in, d_out, d_out_pad, n_chunks, n_jt, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
+  int d_in, n_linears, n_chunks, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
   float z;
 #ifdef MES_TRACE
   unsigned long long* trace;   // development builds only: [call][workgroup][16] timestamps
 #endif
 };
+
+// The linear a row group belongs to.
+__device__ __forceinline__ int linear_of(const LinearParams& p, int rg) {
+  int l = 0;
+#pragma unroll
+  for (int i = 0; i + 1 < kMaxLinears; ++i) l += (i + 1 < p.n_linears && rg >= p.lin[i].rg_end) ? 1 : 0;
+  return l;
+}
 
 #ifdef MES_TRACE
 #define MES_STAMP(i) do { if (threadIdx.x == 0) p.trace[((size_t)(blockIdx.y * gridDim.x + blockIdx.x)) * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
@@ -265,13 +282,16 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     if (q == 0) *reinterpret_cast<int*>(stage + kStageScale + tl * 4) = 128 + s;
     return;
   }
-  if (b < p.n_chunks + p.n_vis) {
+  const int per_linear = p.n_vis + kTokGroup;
+  const int li = (b - p.n_chunks) / per_linear, role = (b - p.n_chunks) - li * per_linear;
+  const PerLinear& L = p.lin[li];
+  if (role < p.n_vis) {
     // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
     // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
     // within 2^-29 of that largest one, and no value overflows.  The main kernel multiplies back.
-    const int v = b - p.n_chunks;
+    const int v = role;
     const int a = p.vis_info[v] & 0xff, tt = p.vis_info[v] >> 8;
-    const int32_t* si = p.sidx[a];
+    const int32_t* si = L.sidx[a];
     __shared__ uint32_t smax[16];
     if (tid < 16) smax[tid] = 0;
     __syncthreads();
@@ -289,7 +309,7 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     if (smax[n] == 0) e = 0;
     e = e < -110 ? -110 : (e > 110 ? 110 : e);
     const float inv = __uint_as_float((uint32_t)(127 - e) << 23);
-    if (inm && tid < 16) p.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
+    if (inm && tid < 16) L.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
     for (int i = tid; i < p.n_sb * 64; i += 256) {
       const int sb = i >> 6;
       u32x4 o;
@@ -301,12 +321,12 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
         if (inm && r0 + 1 < p.k) v1 = bf16_to_f32(xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))]) * inv;
         o[q] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v0) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v1) << 16);
       }
-      p.xs[((size_t)v * p.n_sb + sb) * 64 + lane] = o;
+      L.xs[((size_t)v * p.n_sb + sb) * 64 + lane] = o;
     }
     return;
   }
   // per-token correction  z (sum_i x_i - sum_{salient} x_i)
-  const int tl = b - p.n_chunks - p.n_vis;
+  const int tl = role - p.n_vis;
   const int t = p.t0 + tl;
   __shared__ double red[256];
   double acc = 0.0;
@@ -322,7 +342,7 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     const int a = p.tok_slot[tl];
     if (a != 0xff)
       for (int r = tid; r < p.k; r += 256)
-        acc -= (double)bf16_to_f32(xrow[min((uint32_t)p.sidx[a][r], (uint32_t)(p.d_in - 1))]);
+        acc -= (double)bf16_to_f32(xrow[min((uint32_t)L.sidx[a][r], (uint32_t)(p.d_in - 1))]);
   }
   red[tid] = acc;
   __syncthreads();
@@ -330,7 +350,7 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     if (tid < s) red[tid] += red[tid + s];
     __syncthreads();
   }
-  if (tid == 0) p.corr[tl] = (float)((double)p.z * red[0]);
+  if (tid == 0) L.corr[tl] = (float)((double)p.z * red[0]);
 }
 
 // ---- main kernel ------------------------------------------------------------------------------------
@@ -400,6 +420,7 @@ struct Stream {
   static constexpr int kStageCopies = kStageBlocks / NW;        // copy instructions per wavefront and chunk
 
   const LinearParams& p;
+  const PerLinear& L;
   int lane, n, jt;
   char* parkp;                // this wavefront's LDS area: [NA][kSlotLds]
   uint32_t slot_tok[TT];
@@ -408,7 +429,8 @@ struct Stream {
   CodeRegs<BITS> code[2][NA];
   f32x4 acc_base[TT], acc_raw[TT];
 
-  __device__ __forceinline__ Stream(const LinearParams& p_, int lane_, int jt_, char* park_) : p(p_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_) {
+  __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_)
+      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       slot_tok[tt] = p.tok_slot[16 * tt + n];
@@ -419,7 +441,7 @@ struct Stream {
 
   template <int BUF>
   __device__ __forceinline__ void load_base(int c) {
-    const char* src = p.w_base + ((size_t)c * p.n_jt + jt) * 4096 + lane * 16;
+    const char* src = L.w_base + ((size_t)c * L.n_jt + jt) * 4096 + lane * 16;
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
   }
@@ -433,9 +455,9 @@ struct Stream {
 
   template <int BUF>
   __device__ __forceinline__ void load_code_regs(int c) {
-    const size_t off = ((size_t)c * p.n_jt + jt) * kSlotLds;
+    const size_t off = ((size_t)c * L.n_jt + jt) * kSlotLds;
 #pragma unroll
-    for (int a = 0; a < NA; ++a) load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
+    for (int a = 0; a < NA; ++a) load_codes<BITS>(L.codes[a] + off, lane, code[BUF][a]);
   }
 
   // Register buffer BUF (the chunk that starts now) -> this wavefront's LDS area.
@@ -458,11 +480,11 @@ struct Stream {
   // that was just parked, base weights and scales of chunk cn (one ahead) into the other base buffer.
   template <int BUF>
   __device__ __forceinline__ void request_share(int tt, int cn, int c2) {
-    const size_t off = ((size_t)c2 * p.n_jt + jt) * kSlotLds;
+    const size_t off = ((size_t)c2 * L.n_jt + jt) * kSlotLds;
 #pragma unroll
     for (int a = 0; a < NA; ++a)
-      if (a * TT / NA == tt) load_codes<BITS>(p.codes[a] + off, lane, code[BUF][a]);
-    const char* src = p.w_base + ((size_t)cn * p.n_jt + jt) * 4096 + lane * 16;
+      if (a * TT / NA == tt) load_codes<BITS>(L.codes[a] + off, lane, code[BUF][a]);
+    const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096 + lane * 16;
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb)
       if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
@@ -537,9 +559,10 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int rg = blockIdx.x, sp = blockIdx.y;
-  int jt = rg * NW + wave;
-  const bool live = jt < p.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
-  jt = live ? jt : p.n_jt - 1;
+  const PerLinear& L = p.lin[linear_of(p, rg)];
+  int jt = (rg - L.rg_begin) * NW + wave;
+  const bool live = jt < L.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
+  jt = live ? jt : L.n_jt - 1;
   const int c_begin = (int)((long)sp * p.n_chunks / p.nsplit);
   const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
   MES_STAMP(0);
@@ -551,7 +574,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   __shared__ __attribute__((aligned(16))) char park_all[NW * NA * code_block_bytes(BITS)];
 
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)));
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)));
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -575,14 +598,14 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   f32x4 acc_sal[TT];
   float sal_scale[TT];
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt) { acc_sal[tt] = f32x4{0, 0, 0, 0}; sal_scale[tt] = p.sal_scale[16 * tt + n]; }
+  for (int tt = 0; tt < TT; ++tt) { acc_sal[tt] = f32x4{0, 0, 0, 0}; sal_scale[tt] = L.sal_scale[16 * tt + n]; }
   // What the epilogue needs from memory -- the owning expert's step per output channel and the zero-point
   // correction per token -- sits behind a pointer that depends on the token's slot.  The pointers are
   // fetched here, the values after the wait at the end of this start-up phase; they arrive while the
   // chunks stream.
   const float* step_ptr[TT];
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt) step_ptr[tt] = slot_tok[tt] != 0xffu ? p.step[slot_tok[tt]] : nullptr;
+  for (int tt = 0; tt < TT; ++tt) step_ptr[tt] = slot_tok[tt] != 0xffu ? L.step[slot_tok[tt]] : nullptr;
   if (p.k > 0) {
     constexpr int SD = 8;
     const int n_pairs = p.n_vis * p.n_sb;
@@ -595,8 +618,8 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
     auto request = [&](u32x4& x, u32x4& d, int& tt_out) {
       const int info = p.vis_info[rv];
       tt_out = rleft > 0 ? info >> 8 : -1;
-      x = ld128(reinterpret_cast<const char*>(p.xs) + ((size_t)rv * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
-      d = ld128(p.sal[info & 0xff] + ((size_t)jt * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
+      x = ld128(reinterpret_cast<const char*>(L.xs) + ((size_t)rv * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
+      d = ld128(L.sal[info & 0xff] + ((size_t)jt * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
       if (rleft > 1) {   // past the last pair the same (valid) pair is requested again and ignored
         rsb += p.nsplit;
         while (rsb >= p.n_sb) { rsb -= p.n_sb; ++rv; }
@@ -628,9 +651,9 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     const int j = 16 * jt + 4 * g;
-    corr[tt] = sp == 0 ? p.corr[16 * tt + n] : 0.0f;   // belongs to the whole column range: only the first split applies it
+    corr[tt] = sp == 0 ? L.corr[16 * tt + n] : 0.0f;   // belongs to the whole column range: only the first split applies it
     stepv[tt] = f32x4{0, 0, 0, 0};
-    if (step_ptr[tt] != nullptr && j < p.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(step_ptr[tt] + j);
+    if (step_ptr[tt] != nullptr && j < L.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(step_ptr[tt] + j);
   }
   MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
@@ -662,11 +685,11 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
     const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
-    if (t < p.T && j < p.d_out) {
+    if (t < p.T && j < L.d_out) {
       uint2 pk;
       pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
       pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
-      *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
+      *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
     }
   }
   MES_STAMP(14);
@@ -682,13 +705,14 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p)
   const f32x4* part = p.partial + (size_t)rg * p.nsplit * (4 * NT) + tt * NT + tid;
   f32x4 o = {0, 0, 0, 0};
   for (int s = 0; s < p.nsplit; ++s) o += part[(size_t)s * (4 * NT)];
-  const int jt = rg * NW + wave;
+  const PerLinear& L = p.lin[linear_of(p, rg)];
+  const int jt = (rg - L.rg_begin) * NW + wave;
   const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
-  if (jt < p.n_jt && t < p.T && j < p.d_out) {
+  if (jt < L.n_jt && t < p.T && j < L.d_out) {
     uint2 pk;
     pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
     pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
-    *reinterpret_cast<uint2*>(p.y + (size_t)t * p.d_out + j) = pk;
+    *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
   }
 }
 
@@ -702,20 +726,21 @@ struct Plan {
   int nsplit;  // workgroups that share one row group's columns
 };
 
-// Pure function of the layer shape (not of bits or T), so the workspace size is known up front.
+inline int row_groups_of(int d_out) { return (ceil_to(d_out, kRowPad) / 16 + kWaves - 1) / kWaves; }
+
+// Pure function of the shapes (not of bits or T), so the workspace size is known up front.
 // One workgroup runs per compute unit (256 of them).  The chunks are split over `nsplit` workgroups so that
 // the grid fills the largest part of the last round of 256, with at least four chunks per workgroup and,
 // among equals, few splits (every split writes and re-reads a partial output tile).
-Plan plan_for(int d_in, int d_out) {
-  const int n_jt = ceil_to(d_out, kRowPad) / 16, n_chunks = ceil_to(d_in, kColPad) / kChunk;
+Plan plan_for(int d_in, int total_row_groups) {
+  const int n_chunks = ceil_to(d_in, kColPad) / kChunk;
 #ifdef MES_TRACE
   if (const char* ov = getenv("MES_PLAN")) { Plan o{1}; if (sscanf(ov, "%d", &o.nsplit) == 1) return o; }
 #endif
-  const int rgs = (n_jt + kWaves - 1) / kWaves;
   Plan best{1};
   double best_cost = 1e30;
   for (int ns = 1; ns <= 32 && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
-    const long wgs = (long)rgs * ns;
+    const long wgs = (long)total_row_groups * ns;
     const long rounds = (wgs + 255) / 256;
     const int chunks_wg = (n_chunks + ns - 1) / ns;
     // time ~ rounds x (chunks per workgroup + a fixed start/finish cost of about three chunks) + the partial tiles
@@ -726,19 +751,24 @@ Plan plan_for(int d_in, int d_out) {
 }
 
 struct WorkspaceLayout {
-  size_t xt, xs, corr, partial, total;
+  size_t xt, per_linear[kMaxLinears], partial, total;   // per linear: xs, then corrections and salient scales
+  size_t xs_bytes;
 };
 
-WorkspaceLayout workspace_layout(int d_in, int d_out) {
-  const Plan pl = plan_for(d_in, d_out);
-  const int po = ceil_to(d_out, kRowPad), pi = ceil_to(d_in, kColPad);
+WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
+  int rgs = 0;
+  for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l]);
+  const Plan pl = plan_for(d_in, rgs);
+  const int pi = ceil_to(d_in, kColPad);
   WorkspaceLayout w;
   size_t off = 0;
-  w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes + 1024;   // the copy of the last stage's partial block reads a full KiB
-  w.xs = off;      off += (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
-  w.corr = off;    off += 512;   // corrections, then salient scales
-  const size_t rgs = (size_t)(po / 16 + kWaves - 1) / kWaves;
-  w.partial = off; off += pl.nsplit > 1 ? rgs * pl.nsplit * 4 * (64 * kWaves) * 16 : 0;
+  w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes;
+  w.xs_bytes = (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
+  for (int l = 0; l < kMaxLinears; ++l) {
+    w.per_linear[l] = off;
+    if (l < n_linears) off += w.xs_bytes + 512;
+  }
+  w.partial = off; off += pl.nsplit > 1 ? (size_t)rgs * pl.nsplit * 4 * (64 * kWaves) * 16 : 0;
   w.total = off;
   return w;
 }
@@ -766,15 +796,16 @@ unsigned long long* g_trace = nullptr;
 int g_call = 0;
 #endif
 
-size_t linear_workspace_bytes(int d_in, int d_out, int max_tokens) {
+size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
   (void)max_tokens;  // one 64-token group is in flight at a time
-  return workspace_layout(d_in, d_out).total;
+  return workspace_layout(d_in, d_out, n_linears).total;
 }
 
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
-  const mes_delta& d0 = c.experts[0];
-  const Plan pl = plan_for(d0.d_in, d0.d_out);
-  const WorkspaceLayout wl = workspace_layout(d0.d_in, d0.d_out);
+  const mes_delta& d0 = c.lin[0].experts[0];
+  int d_outs[kMaxLinears];
+  for (int l = 0; l < c.n_linears; ++l) d_outs[l] = c.lin[l].experts[0].d_out;
+  const WorkspaceLayout wl = workspace_layout(d0.d_in, d_outs, c.n_linears);
   char* ws = reinterpret_cast<char*>(c.ws);
   LinearParams p;
 #ifdef MES_TRACE
@@ -782,27 +813,35 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.trace = g_trace + (size_t)(g_call % 64) * (1 << 17);
   ++g_call;
 #endif
-  p.w_base = reinterpret_cast<const char*>(c.w_base);
   p.x = reinterpret_cast<const uint16_t*>(c.x);
-  p.y = reinterpret_cast<uint16_t*>(c.y);
   p.xt = ws + wl.xt;
-  p.xs = reinterpret_cast<u32x4*>(ws + wl.xs);
-  p.corr = reinterpret_cast<float*>(ws + wl.corr);
-  p.sal_scale = p.corr + kTokGroup;
   p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
-  const int po = ceil_to(d0.d_out, kRowPad), pi = ceil_to(d0.d_in, kColPad);
+  const int pi = ceil_to(d0.d_in, kColPad);
   p.d_in = d0.d_in;
-  p.d_out = d0.d_out;
-  p.d_out_pad = po;
+  p.n_linears = c.n_linears;
   p.n_chunks = pi / kChunk;
-  p.n_jt = po / 16;
   p.n_sb = ceil_to(d0.k, kSalPad) / 32;
   p.k = d0.k;
-  p.T = c.T;
-  p.nsplit = pl.nsplit;
   p.bits = d0.bits;
   p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
-  const dim3 grid((p.n_jt + kWaves - 1) / kWaves, pl.nsplit);
+  int rgs = 0;
+  for (int l = 0; l < kMaxLinears; ++l) {
+    PerLinear& L = p.lin[l];
+    const int ll = l < c.n_linears ? l : 0;   // unused entries repeat the first (never selected)
+    L.w_base = reinterpret_cast<const char*>(c.lin[ll].w_base_tiled);
+    L.y = reinterpret_cast<uint16_t*>(c.lin[ll].y);
+    L.xs = reinterpret_cast<u32x4*>(ws + wl.per_linear[ll]);
+    L.corr = reinterpret_cast<float*>(ws + wl.per_linear[ll] + wl.xs_bytes);
+    L.sal_scale = L.corr + kTokGroup;
+    L.d_out = d_outs[ll];
+    L.n_jt = ceil_to(d_outs[ll], kRowPad) / 16;
+    L.rg_begin = rgs;
+    if (l < c.n_linears) rgs += row_groups_of(d_outs[l]);
+    L.rg_end = rgs;
+  }
+  const Plan pl = plan_for(d0.d_in, rgs);
+  p.nsplit = pl.nsplit;
+  const dim3 grid(rgs, pl.nsplit);
   // Token groups: up to 64 consecutive tokens that belong to at most max_pass_slots experts.
   const int max_slots = max_pass_slots(d0.bits);
   int e_cur = 0;   // first expert that may own token t0
@@ -825,17 +864,23 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       const int lo = (c.seg[e] > t0 ? c.seg[e] : t0) - t0;
       const int hi = (c.seg[e + 1] < t0 + nt ? c.seg[e + 1] : t0 + nt) - t0;
       if (hi <= lo) continue;
-      p.codes[na] = reinterpret_cast<const char*>(c.experts[e].codes);
-      p.step[na] = c.experts[e].step;
-      p.sal[na] = reinterpret_cast<const char*>(c.experts[e].salient);
-      p.sidx[na] = c.experts[e].salient_idx;
+      for (int l = 0; l < kMaxLinears; ++l) {
+        const mes_delta& d = c.lin[l < c.n_linears ? l : 0].experts[e];
+        p.lin[l].codes[na] = reinterpret_cast<const char*>(d.codes);
+        p.lin[l].step[na] = d.step;
+        p.lin[l].sal[na] = reinterpret_cast<const char*>(d.salient);
+        p.lin[l].sidx[na] = d.salient_idx;
+      }
       p.lo[na] = (int16_t)lo;
       p.hi[na] = (int16_t)hi;
       for (int tl = lo; tl < hi; ++tl) p.tok_slot[tl] = (uint8_t)na;
       ++na;
     }
     for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
-      p.codes[a] = p.codes[0]; p.step[a] = p.step[0]; p.sal[a] = p.sal[0]; p.sidx[a] = p.sidx[0];
+      for (int l = 0; l < kMaxLinears; ++l) {
+        PerLinear& L = p.lin[l];
+        L.codes[a] = L.codes[0]; L.step[a] = L.step[0]; L.sal[a] = L.sal[0]; L.sidx[a] = L.sidx[0];
+      }
       p.lo[a] = 0; p.hi[a] = 0;
     }
     // visits, tile-major: for every 16-token tile the slots that own tokens in it
@@ -857,15 +902,17 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
     p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
-    k_prepare<<<p.n_chunks + p.n_vis + kTokGroup, 256, 0, s>>>(p);
+    k_prepare<<<p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (c.ev_start && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
     switch (d0.bits) {
       case 1: e = launch_na<1>(p, tt, grid, s); break;
       case 2: e = launch_na<2>(p, tt, grid, s); break;
       default: e = launch_na<3>(p, tt, grid, s); break;
     }
     if (e != hipSuccess) return e;
+    if (c.ev_stop && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;
     if (pl.nsplit > 1) {
       k_reduce_splits<kWaves><<<dim3(grid.x, tt), 64 * kWaves, 0, s>>>(p);
       if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -214,6 +214,32 @@ def test_special_cases_reduce_to_dense_products():
     assert rel_fro(y, ref) <= TOL
 
 
+@pytest.mark.parametrize("d_in,d_outs,seg,k,bits", [
+    (512, [128, 64, 72], [0, 9, 21, 40], 8, 2),          # three layers of different widths, one launch
+    (1032, [132, 256], [0, 1, 2, 3, 64], 33, 3),          # ragged widths, 3-bit, 64 tokens
+    (4096, [320, 192, 64], [0, 7, 30, 31, 50, 61], 64, 2),   # column splits across the fused row groups
+])
+def test_fused_layers_match_the_oracle_and_the_single_calls(d_in, d_outs, seg, k, bits):
+    """Several layers reading the same activations through one mes_delta_linear_multi call: every layer within
+    tolerance of the oracle, and as close to its own single-layer call as two fp32 summation orders can be."""
+    wls = [synth.small_case(d_in, d, seg, k, bits, seed=100 + 7 * i + d_in % 97) for i, d in enumerate(d_outs)]
+    x = wls[0].x
+    layers, oes = [], []
+    for wl in wls:
+        wl.x = x                                           # the same activations for every layer
+        layers.append((mes.mes_pack_base(wl.w_base.to(DEV)), gpu_experts(wl)))
+        oes.append(oracle_experts(wl))
+    fused = mes.DeltaLinearMulti(layers, 64)
+    ys = fused(x.to(DEV), seg)
+    torch.cuda.synchronize()
+    for wl, (w_t, ge), oe, y in zip(wls, layers, oes, ys):
+        y_ref = O.delta_linear(x.double().numpy(), wl.w_base.double().numpy(), oe, seg)
+        assert y.shape == (seg[-1], wl.d_out)
+        assert rel_fro(y, y_ref) <= TOL
+        y_single = mes.mes_delta_linear(w_t, ge, x.to(DEV), seg)
+        assert rel_fro(y, y_single.double().cpu().numpy()) <= 4e-3   # both are one bf16 rounding away from the same sum
+
+
 def test_config2_full_size():
     """Mistral-7B q_proj shape, 3 experts, 16/16/16 decode tokens; full output against the oracle."""
     y, y_ref = run_case(synth.config2())

@@ -116,6 +116,30 @@ def test_delta_linear_argument_errors():
     assert lib.mes_delta_linear(FAKE, arr, 65, FAKE, 4, (ctypes.c_int32 * 2)(0, 4), FAKE, FAKE, 1 << 30, None) == 2
 
 
+def test_delta_linear_multi_argument_errors():
+    d = _desc()
+    arr = (B.mes_delta * 2)(d, d)
+    wide = (B.mes_delta * 2)(_desc(d_out=128), _desc(d_out=128))
+    seg = (ctypes.c_int32 * 3)(0, 2, 4)
+
+    def call(layers, n=None, T=4, ws=FAKE, wsb=1 << 30, x=FAKE):
+        lin = (B.mes_linear * len(layers))(*layers)
+        return lib.mes_delta_linear_multi(lin, len(layers) if n is None else n, 2, x, T, seg, ws, wsb, None)
+    ok = B.mes_linear(FAKE, arr, FAKE)
+    assert call([ok, B.mes_linear(FAKE, wide, FAKE)], wsb=4) == 7          # two layers of different widths: fine up to the workspace
+    assert call([ok], n=0) == 2 and call([ok] * 4) == 2                    # 1 .. MES_MAX_FUSED layers
+    assert call([ok, B.mes_linear(None, arr, FAKE)]) == 1
+    assert call([ok, B.mes_linear(FAKE, arr, None)]) == 1
+    assert call([ok, B.mes_linear(FAKE, arr, ODD)]) == 6
+    other_k = (B.mes_delta * 2)(_desc(k=8), _desc(k=8))
+    assert call([ok, B.mes_linear(FAKE, other_k, FAKE)]) == 2              # k must agree across layers
+    mixed = (B.mes_delta * 2)(_desc(d_out=128), _desc(d_out=64))
+    assert call([B.mes_linear(FAKE, mixed, FAKE)]) == 2                    # experts of one layer must agree on d_out
+    d2 = (ctypes.c_int32 * 2)(64, 128)
+    assert lib.mes_linear_multi_workspace_bytes(64, d2, 2, 64) > lib.mes_linear_workspace_bytes(64, 64, 64)
+    assert lib.mes_linear_multi_workspace_bytes(64, d2, 4, 64) == 0
+
+
 def test_unpack_and_workspace_init_argument_errors():
     d = _desc()
     assert lib.mes_unpack_delta(ctypes.byref(d), None, None, None) == 1
