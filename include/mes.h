@@ -176,7 +176,7 @@ mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, 
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Measurement hook (for benchmarks; Section 5.4's latency figures time the layer, this times its dominant
+/* Measurement hook (for benchmarks; the latency analysis of Section 5.2 times the layer, this times its dominant
  * kernel): the NEXT mes_delta_linear / mes_delta_linear_multi call of the calling thread records `start_event`
  * on its stream immediately before its streaming kernel and `stop_event` immediately after it (hipEvent_t
  * passed as void*, HOST handles owned by the caller; with more than one token group the last group's).

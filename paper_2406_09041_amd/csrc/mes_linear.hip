@@ -38,9 +38,6 @@
 // where a run-time slot number can index them.
 #include "mes_internal.h"
 
-#ifndef MES_EXP
-#define MES_EXP 0
-#endif
 #ifdef MES_TRACE
 #include <cstdio>
 #include <cstdlib>
@@ -509,15 +506,9 @@ struct Stream {
 #define MES_CSTAMP(i) do { } while (0)
 #endif
     MES_CSTAMP(2);
-#if MES_EXP == 2
-    cn = 0; c2 = 0;
-#endif
     park<BUF>();
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
     MES_CSTAMP(3);
-#if MES_EXP == 3
-    if (false)
-#endif
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       // this tile's share of the next chunks' requests: spreading them over the chunk keeps the memory
@@ -543,7 +534,6 @@ struct Stream {
       }
       MES_CSTAMP(4 + tt);
     }
-    __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(kYounger));
     MES_CSTAMP(8);
     stage_barrier<kYounger>();
     MES_CSTAMP(9);
