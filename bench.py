@@ -68,7 +68,7 @@ def main():
     if args.workload == "c4":
         names = [n for n, _, _ in synth.MISTRAL7B_LINEARS]
         wls = [(n, lambda n=n: synth.config4_linear(n, device=dev, bits=args.bits)) for n in names]
-        sample_frac = 8
+        sample_frac = 2
         copies = 1
     else:
         # 48 MB per call fits the 256 MB Infinity Cache: rotate over independent copies so every call streams from HBM
@@ -110,6 +110,8 @@ def main():
             calls.append(dict(name=L["name"], bytes=L["bytes"],
                               run=(lambda L=L: L["lin"](L["x"], L["seg"], L["y"]))))
         else:
+            assert all(torch.equal(L["x"], Ls[0]["x"]) and L["seg"] == Ls[0]["seg"] for L in Ls), \
+                "fused layers must read the same activations and routing"
             fused = mes.DeltaLinearMulti([(L["lin"].w, L["lin"].experts) for L in Ls], T)
             ys = [L["y"] for L in Ls]
             # the shared activations are read (and credited) once

@@ -132,14 +132,16 @@ def make_delta(d_in: int, d_out: int, k: int, std: float, outlier_scale: float,
 def make_linear(name: str, d_in: int, d_out: int, n_experts: int, seg_offsets: Sequence[int],
                 k: int, bits: int, config_id: int, layer: int = 0, *,
                 base_std: float = 0.02, delta_std: float = 0.003, outlier_scale: float = 15.0,
-                x_std: float = 1.0, device: str = "cpu", shape_id: int = 0) -> LinearWorkload:
-    """One linear layer's worth of synthetic data for `n_experts` experts."""
+                x_std: float = 1.0, device: str = "cpu", shape_id: int = 0,
+                x_id: Optional[int] = None) -> LinearWorkload:
+    """One linear layer's worth of synthetic data for `n_experts` experts.  Layers given the same `x_id`
+    (and input width) draw the same activations."""
     T = int(seg_offsets[-1])
     sid = shape_id * 16
     w_base = normal((d_out, d_in), base_std, seed_for(config_id, layer, 0, 1 + sid), device, torch.bfloat16)
     experts = [make_delta(d_in, d_out, k, delta_std, outlier_scale,
                           seed_for(config_id, layer, e, 2 + sid), device) for e in range(n_experts)]
-    x = normal((T, d_in), x_std, seed_for(config_id, layer, 0, 3 + sid), device, torch.bfloat16)
+    x = normal((T, d_in), x_std, seed_for(config_id, layer, 0, 3 + (sid if x_id is None else 16 * x_id)), device, torch.bfloat16)
     return LinearWorkload(name, d_in, d_out, w_base, experts, x, list(map(int, seg_offsets)), bits, k,
                           {"config_id": config_id, "layer": layer})
 
@@ -172,12 +174,14 @@ def config4_routing(n_tokens: int = 64, n_experts: int = 16, layer: int = 0):
 
 def config4_linear(which: str, device: str = "cpu", layer: int = 0, n_tokens: int = 64,
                    n_experts: int = 16, bits: int = 2, k: int = 64) -> LinearWorkload:
-    """One of the seven Mistral-7B linear shapes, 16 experts, Zipf-routed decode batch."""
+    """One of the seven Mistral-7B linear shapes, 16 experts, Zipf-routed decode batch.  The shapes do not
+    chain, so every layer of one input width reads the same fixed activations (one batch 4096 wide for six
+    of them, one 14336 wide for down_proj)."""
     shapes = {n: (i, di, do) for i, (n, di, do) in enumerate(MISTRAL7B_LINEARS)}
     sid, d_in, d_out = shapes[which]
     _, off = config4_routing(n_tokens, n_experts, layer)
     return make_linear(f"c4_{which}", d_in, d_out, n_experts, off, k, bits, 4, layer=layer,
-                       device=device, shape_id=sid)
+                       device=device, shape_id=sid, x_id=(0 if d_in == 4096 else 1))
 
 
 def small_case(d_in: int, d_out: int, seg_offsets: Sequence[int], k: int, bits: int,
