@@ -36,6 +36,45 @@ def algorithmic_bytes(d_in, d_out, k, bits, n_active, T):
     return base + n_active * per_expert + 2 * T * d_in + 2 * T * d_out
 
 
+COPY_PROBE_BYTES = 1 << 30
+
+
+def write_traffic(args):
+    """HBM bytes per k_delta_linear launch from hardware counters.  Each counter's reading for the streaming
+    kernel is scaled by the same counter's reading for k_copy_probe, which moves a known number of bytes."""
+    import csv
+    import glob
+
+    def mean_by_kernel(folder, counter):
+        files = glob.glob(os.path.join(folder, "**", "*counter_collection.csv"), recursive=True)
+        assert files, f"no counter_collection.csv under {folder}"
+        acc = {}
+        for r in csv.DictReader(open(files[0])):
+            if r["Counter_Name"] != counter:
+                continue
+            for key in ("k_delta_linear", "k_copy_probe"):
+                if key in r["Kernel_Name"]:
+                    acc.setdefault(key, []).append(float(r["Counter_Value"]))
+        assert "k_delta_linear" in acc and "k_copy_probe" in acc, f"{counter}: kernels missing in {files[0]}"
+        return {k: (sum(v) / len(v), len(v)) for k, v in acc.items()}
+
+    fetch = mean_by_kernel(args.traffic_from[0], "FETCH_SIZE")
+    write = mean_by_kernel(args.traffic_from[1], "WRITE_SIZE")
+    f_scale = COPY_PROBE_BYTES / fetch["k_copy_probe"][0]      # bytes per counter unit, from the copy kernel
+    w_scale = COPY_PROBE_BYTES / write["k_copy_probe"][0]
+    rd = fetch["k_delta_linear"][0] * f_scale
+    wr = write["k_delta_linear"][0] * w_scale
+    key = f"{args.workload}_b{args.bits}"
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    table = json.load(open(path)) if os.path.exists(path) else {}
+    table[key] = {"bytes_per_launch": int(rd + wr), "read_bytes_per_launch": int(rd), "write_bytes_per_launch": int(wr),
+                  "launches": fetch["k_delta_linear"][1], "fetch_bytes_per_unit": round(f_scale, 3),
+                  "write_bytes_per_unit": round(w_scale, 3), "copy_probe_bytes": COPY_PROBE_BYTES,
+                  "unfused": bool(args.unfused)}
+    json.dump(table, open(path, "w"), indent=1, sort_keys=True)
+    print(json.dumps({key: table[key]}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,7 +85,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every call on its own (stderr)")
     ap.add_argument("--unfused", action="store_true", help="seven single-layer calls per step instead of four")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the measurements run the library's plain copy kernel on 1 GiB (counter calibration)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
+                    help="no GPU work: read the counter CSVs of two `rocprofv3 --pmc` runs of this script with "
+                         "--copy-probe (FETCH_SIZE, then WRITE_SIZE) and write profiles/traffic.json")
     args = ap.parse_args()
+    if args.traffic_from:
+        write_traffic(args)
+        return
     if args.gpus != 1:
         print("bench.py: this build measures ONE GPU; --gpus must be 1 (nothing here uses a second GPU).", file=sys.stderr)
         sys.exit(2)
@@ -173,6 +220,14 @@ def main():
         breakdown = {c["name"]: dict(kernel_us=round(kernel_us[ci] / reps, 2), MB=round(c["bytes"] / 1e6, 2),
                                      GBs=round(c["bytes"] / (kernel_us[ci] / reps) / 1e3, 1)) for ci, c in enumerate(calls)}
         print("breakdown:", json.dumps(breakdown), file=sys.stderr)
+
+    if args.copy_probe:
+        src = torch.empty(COPY_PROBE_BYTES, dtype=torch.uint8, device=dev).random_(0, 256)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            mes.mes_copy_probe(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- oracle leg (baseline only)
     cpu_baseline = None

@@ -183,6 +183,12 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
  * One-shot; two NULLs cancel. */
 mes_status mes_time_next_call(void* start_event, void* stop_event);
 
+/* Measurement hook: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers DEVICE,
+ * 16-byte aligned, not overlapping) done by one kernel, k_copy_probe.  It reads and writes exactly `bytes`
+ * of HBM, which is what a profiler's memory-traffic counters are scaled by before they are compared with the
+ * streaming kernel's algorithmic bytes. */
+mes_status mes_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_select_workspace_bytes", "mes_linear_workspace_bytes", "mes_last_error", "mes_layout_version",
            "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
            "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
-           "mes_delta_linear_multi", "mes_time_next_call"]
+           "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe"]
 
 
 class MesError(RuntimeError):
@@ -91,6 +91,8 @@ def _load() -> ctypes.CDLL:
                                            ctypes.POINTER(ctypes.c_int32), vp, c_sz, vp]
     lib.mes_time_next_call.restype = c_int
     lib.mes_time_next_call.argtypes = [vp, vp]
+    lib.mes_copy_probe.restype = c_int
+    lib.mes_copy_probe.argtypes = [vp, vp, c_sz, vp]
     return lib
 
 
@@ -123,6 +125,12 @@ def mes_pack_base(w: torch.Tensor) -> torch.Tensor:
     out = torch.empty(base_bytes(d_in, d_out), dtype=torch.uint8, device=w.device)
     _check(lib.mes_pack_base(_ptr(w), d_in, d_out, _ptr(out), _stream(w.device)))
     return out
+
+
+def mes_copy_probe(dst: torch.Tensor, src: torch.Tensor) -> None:
+    """Plain copy kernel of known traffic (src.nbytes read, as many written); see mes_copy_probe in mes.h."""
+    assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous() and dst.nbytes == src.nbytes
+    _check(lib.mes_copy_probe(_ptr(dst), _ptr(src), src.nbytes, _stream(src.device)))
 
 
 def mes_unpack_base(w_tiled: torch.Tensor, d_in: int, d_out: int) -> torch.Tensor:

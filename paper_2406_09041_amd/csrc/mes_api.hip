@@ -224,4 +224,10 @@ mes_status mes_time_next_call(void* start_event, void* stop_event) {
   return MES_OK;
 }
 
+mes_status mes_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src) return fail(MES_ERR_NULL, "mes_copy_probe: null buffer");
+  if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return fail(MES_ERR_ALIGN, "mes_copy_probe: buffers and size must be multiples of 16 bytes");
+  return check_hip(launch_copy_probe(dst, src, bytes, (hipStream_t)stream), "mes_copy_probe");
+}
+
 }  // extern "C"

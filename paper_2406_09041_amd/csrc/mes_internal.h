@@ -30,6 +30,7 @@ hipError_t launch_unpack_delta(const mes_delta& d, float* delta_hat, uint8_t* co
 hipError_t launch_select(const float* delta, const float* xc, int n, int d_in, int d_out, int bits, int grid,
                          int policy, int k, int32_t* idx_out, double* score_out, void* ws, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // ---- launcher implemented in mes_linear.hip -----------------------------------------------------
 struct LinearCall {

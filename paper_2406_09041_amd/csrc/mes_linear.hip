@@ -569,11 +569,12 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
 
-  // The chunks of the range are visited from a start that differs from row group to row group (the sum
-  // does not care about the order), so that workgroups running side by side do not march in lockstep
-  // through the same columns.
+  // The chunks of the range are visited from a start that differs from XCD to XCD (the sum does not care
+  // about the order; workgroups go round-robin to the 8 XCDs, so rg & 7 names the XCD): the XCDs do not
+  // march in lockstep through the same columns, while the workgroups that share one XCD's L2 read the same
+  // activation stage at about the same time and fetch it from memory once.
   const int len = c_end - c_begin;
-  const int rot = len > 0 ? (int)((((uint32_t)rg * 2654435761u) >> 12) % (uint32_t)len) : 0;
+  const int rot = ((rg & 7) * len) >> 3;
   auto chunk_at = [&](int i) { i = i < len ? i : len - 1; int r = i + rot; r = r >= len ? r - len : r; return c_begin + r; };
   // first chunks' activations and weights: requested now, needed after the salient product below
   stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);

@@ -291,6 +291,19 @@ hipError_t launch_unpack_base(const uint16_t* t, int d_in, int d_out, uint16_t* 
   return hipGetLastError();
 }
 
+// Plain streaming copy, 16 bytes per thread and iteration: the yardstick the HBM byte counters are scaled by.
+__global__ __launch_bounds__(256) void k_copy_probe(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_copy_probe(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  k_copy_probe<<<(unsigned)(blocks_for(n, 256) < 8192 ? blocks_for(n, 256) : 8192), 256, 0, s>>>(
+      reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), n);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   size_t n = bytes / 4;
   if (n == 0) return hipSuccess;

@@ -240,6 +240,14 @@ def test_fused_layers_match_the_oracle_and_the_single_calls(d_in, d_outs, seg, k
         assert rel_fro(y, y_single.double().cpu().numpy()) <= 4e-3   # both are one bf16 rounding away from the same sum
 
 
+def test_copy_probe_copies():
+    src = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    dst = torch.zeros_like(src)
+    mes.mes_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+
+
 def test_config2_full_size():
     """Mistral-7B q_proj shape, 3 experts, 16/16/16 decode tokens; full output against the oracle."""
     y, y_ref = run_case(synth.config2())

@@ -148,6 +148,13 @@ def test_unpack_and_workspace_init_argument_errors():
     assert lib.mes_workspace_init(ODD, 64, None) == 6
 
 
+def test_copy_probe_argument_errors():
+    lib = B.lib
+    assert lib.mes_copy_probe(None, 16, 16, None) == 1
+    assert lib.mes_copy_probe(32, 16, 24, None) == 6
+    assert lib.mes_copy_probe(32, 24, 16, None) == 6
+
+
 def test_no_cpu_fallback_in_the_product_path():
     """The binding and the library sources never import or include the oracle."""
     pkg = os.path.join(ROOT, "paper_2406_09041_amd")
