@@ -269,3 +269,68 @@ def test_config4_sampled_rows_at_full_size():
     err = rel_fro(y[:, rows.to(DEV)], y_ref)
     assert err <= TOL
     assert sum(1 for e in range(16) if wl.seg_offsets[e + 1] > wl.seg_offsets[e]) >= 8
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3])
+def test_more_experts_than_one_pass_holds(bits):
+    """40 experts, most with one or two tokens, in one 64-token batch: the token group has to be cut where the
+    kernel's expert slots run out (16, or 10 at 3 bits), with empty experts sprinkled in."""
+    seg = [0]
+    for e in range(40):
+        seg.append(seg[-1] + (1, 2, 0, 1, 3, 1, 2, 1)[e % 8])      # 55 tokens, 35 experts with tokens
+    wl = synth.small_case(640, 80, seg, 24, bits, seed=40 + bits)
+    y, y_ref = run_case(wl)
+    assert rel_fro(y, y_ref) <= TOL
+    yg = y.double().cpu().numpy()
+    row_err = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert row_err.max() <= 2 * TOL
+
+
+def sampled_rows_check(wl, y, n_rows, seed):
+    g = torch.Generator().manual_seed(seed)
+    rows = torch.sort(torch.randperm(wl.d_out, generator=g)[:n_rows]).values.to(DEV)
+    oe = oracle_experts(wl, rows=rows)
+    y_ref = O.delta_linear(wl.x.double().cpu().numpy(), wl.w_base[rows].double().cpu().numpy(), oe, wl.seg_offsets)
+    return rel_fro(y[:, rows], y_ref)
+
+
+@pytest.mark.parametrize("bits,which", [(1, "down_proj"), (3, "down_proj"), (3, "q_proj")])
+def test_config4_other_bit_widths_at_full_size(bits, which):
+    """The 1- and 3-bit code paths at a full Mistral-7B shape with 16 experts (the 14336-wide input of
+    down_proj is the longest reduction any config has)."""
+    wl = synth.config4_linear(which, device=DEV, bits=bits)
+    w_t = mes.mes_pack_base(wl.w_base)
+    ge = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]
+    y = mes.mes_delta_linear(w_t, ge, wl.x, wl.seg_offsets)
+    torch.cuda.synchronize()
+    assert sampled_rows_check(wl, y, 96, 5 + bits) <= TOL
+
+
+def test_config4_fused_calls_at_full_size():
+    """The launch configuration the benchmark times: q+k+v in one call and gate+up in one call, 16 experts,
+    64 Zipf-routed tokens, every layer checked on sampled output channels."""
+    for names in (["q_proj", "k_proj", "v_proj"], ["gate_proj", "up_proj"]):
+        wls = [synth.config4_linear(n, device=DEV) for n in names]
+        assert all(torch.equal(w.x, wls[0].x) for w in wls)
+        layers = [(mes.mes_pack_base(w.w_base), [mes.mes_pack_delta(ex.delta, ex.salient_idx, w.bits) for ex in w.experts])
+                  for w in wls]
+        ys = mes.DeltaLinearMulti(layers, 64)(wls[0].x, wls[0].seg_offsets)
+        torch.cuda.synchronize()
+        for i, (w, y) in enumerate(zip(wls, ys)):
+            assert y.shape == (64, w.d_out)
+            assert sampled_rows_check(w, y, 64, 300 + i) <= TOL
+        del wls, layers, ys
+        torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("bits,which", [(2, "gate_proj"), (3, "down_proj")])
+def test_config3_prefill_sampled_rows(bits, which):
+    """Three experts with one 512-token sequence each (24 token groups over the same weights), 128 salient
+    channels; the oracle recomputes sampled output channels for all 1536 tokens."""
+    wl = synth.config3(which, bits=bits, device=DEV)
+    w_t = mes.mes_pack_base(wl.w_base)
+    ge = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]
+    y = mes.mes_delta_linear(w_t, ge, wl.x, wl.seg_offsets)
+    torch.cuda.synchronize()
+    assert y.shape == (1536, wl.d_out)
+    assert sampled_rows_check(wl, y, 64, 11 + bits) <= TOL
