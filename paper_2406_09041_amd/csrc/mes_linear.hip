@@ -125,7 +125,7 @@ __device__ __forceinline__ void mfma_fp4_fp8_pair(f32x4& acc, u32x4 a, v8i bhi, 
   asm volatile("s_nop 1\n\t"
                "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4\n\t"
                "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %3, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4"
-               : "+a"(acc) : "v"(a), "v"(bhi), "v"(blo), "v"(127), "v"(scale_b));
+               : "+v"(acc) : "v"(a), "v"(bhi), "v"(blo), "v"(127), "v"(scale_b));
 }
 
 // Code words of one slot for one (chunk, row tile): LW low words per lane and, for b = 3, one word of high bits.
