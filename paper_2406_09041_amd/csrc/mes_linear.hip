@@ -382,10 +382,10 @@ __device__ __forceinline__ v8i lds_fp8(const char* stage, int tt, int piece, int
 // because it cannot tell that they go to the stage nobody reads yet.  stage_barrier() does the waiting.
 template <int NW>
 __device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, int wave, int lane) {
-  static_assert(kStageBlocks % NW == 0, "the stage copy is dealt evenly to the wavefronts");
 #pragma unroll
-  for (int i = 0; i < kStageBlocks / NW; ++i) {
+  for (int i = 0; i < (kStageBlocks + NW - 1) / NW; ++i) {
     const int blk = wave + NW * i;
+    if (kStageBlocks % NW != 0 && blk >= kStageBlocks) break;   // 32 blocks dealt round-robin: some wavefronts carry one more
     const char* g = src + blk * 1024 + lane * 16;
     const uint32_t l = (uint32_t)(uintptr_t)(dst_lds + blk * 1024);   // LDS byte address; the hardware adds 16 * lane
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
@@ -414,7 +414,6 @@ __device__ __forceinline__ void stage_barrier() {
 template <int BITS, int TT, int NA, int NW>
 struct Stream {
   static constexpr int kSlotLds = code_block_bytes(BITS);       // LDS bytes of one parked slot
-  static constexpr int kStageCopies = kStageBlocks / NW;        // copy instructions per wavefront and chunk
 
   const LinearParams& p;
   const PerLinear& L;
@@ -426,13 +425,64 @@ struct Stream {
   CodeRegs<BITS> code[2][NA];
   f32x4 acc_base[TT], acc_raw[TT];
 
-  __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_)
-      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_) {
+  // Salient fp16 columns ride along with the stream: the (visit, 32-column block) pairs of this workgroup
+  // (pairs sp, sp + nsplit, ... of n_vis * n_sb) are dealt kSalPerChunk to a chunk, requested one chunk before
+  // they are multiplied.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
+  static constexpr int kSalPerChunk = 1;
+  const float2* tok;   // LDS, per token: .x zero-point correction, .y the power of two its salient activations were divided by
+  u32x4 sal_x[kSalPerChunk], sal_d[kSalPerChunk];
+  int sal_tt[kSalPerChunk];
+  int sal_v, sal_sb, sal_left;   // (visit, block) of the next pair to request; pairs not yet requested
+
+  __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_,
+                                    const float2* tok_)
+      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_), tok(tok_) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       slot_tok[tt] = p.tok_slot[16 * tt + n];
       acc_base[tt] = f32x4{0, 0, 0, 0};
       acc_raw[tt] = f32x4{0, 0, 0, 0};
+    }
+  }
+
+  __device__ __forceinline__ void sal_begin(int sp) {
+    const int n_pairs = p.n_vis * p.n_sb;
+    sal_left = n_pairs > sp ? (n_pairs - sp + p.nsplit - 1) / p.nsplit : 0;
+    sal_v = 0;
+    sal_sb = sp;
+    while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
+  }
+
+  // Requests the next pair (always two loads, so that the number of loads in flight does not depend on the
+  // data: once the pairs are used up both read the start of the activation stages and tt_out = -1).
+  __device__ __forceinline__ void sal_request(u32x4& x, u32x4& d, int& tt_out) {
+    const bool more = sal_left > 0;
+    const int info = p.vis_info[more ? sal_v : 0];
+    tt_out = more ? info >> 8 : -1;
+    const char* xp = more ? reinterpret_cast<const char*>(L.xs) + ((size_t)sal_v * p.n_sb + sal_sb) * 1024 : p.xt;
+    const char* dp = more ? L.sal[info & 0xff] + ((size_t)jt * p.n_sb + sal_sb) * 1024 : p.xt;
+    x = ld128(xp, (uint32_t)lane * 16u);
+    d = ld128(dp, (uint32_t)lane * 16u);
+    if (more) {
+      --sal_left;
+      sal_sb += p.nsplit;
+      while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
+    }
+  }
+
+  // The pair's 16 x 16 product goes to the base accumulators of its token tile, times the tokens' scale.  Which
+  // tile that is is known only at run time; rather than branch around four matrix instructions (which makes
+  // the compiler keep two copies of every accumulator), the product is formed once and added everywhere with
+  // a factor that is zero for the other tiles.
+  __device__ __forceinline__ void sal_multiply(int i) {
+    const f32x4 t = mfma_f16(sal_d[i], sal_x[i], f32x4{0, 0, 0, 0});
+    const int stt = sal_tt[i];
+    const float ss = stt >= 0 ? tok[16 * (stt >= 0 ? stt : 0) + n].y : 0.0f;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      const float m = tt == stt ? ss : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc_base[tt][v] += t[v] * m;
     }
   }
 
@@ -495,7 +545,7 @@ struct Stream {
   }
 
   // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
-  static constexpr int kYounger = NA * (BITS == 3 ? 2 : 1) + 4 + TT;
+  static constexpr int kYounger = NA * (BITS == 3 ? 2 : 1) + 4 + TT + 2 * kSalPerChunk;
 
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
   template <int BUF>
@@ -523,7 +573,10 @@ struct Stream {
       for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
-      for (int a = first; a <= last; ++a) {
+      // every tile of the launch has at least one visit (the host gives an empty tile slot 0, whose tokens
+      // are nobody's: scale 0), so there is no branch around the loop and no second copy of the accumulator
+      int a = first;
+      do {
         const int sc = slot_tok[tt] == (uint32_t)a ? scale[BUF][tt] : 0;
         const u32x4 d = dequant_lo<BITS>(cr);
         u32x4 h;
@@ -531,8 +584,14 @@ struct Stream {
         cr = parked(a < last ? a + 1 : a);   // the next visit's words, fetched while this one multiplies
         mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
         if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
-      }
+      } while (++a <= last);
       MES_CSTAMP(4 + tt);
+    }
+    // this chunk's salient pairs (requested a chunk ago), and the requests for the next chunk's
+#pragma unroll
+    for (int i = 0; i < kSalPerChunk; ++i) {
+      sal_multiply(i);
+      sal_request(sal_x[i], sal_d[i], sal_tt[i]);
     }
     MES_CSTAMP(8);
     stage_barrier<kYounger>();
@@ -563,8 +622,12 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // parked code words: one private area per wavefront
   __shared__ __attribute__((aligned(16))) char park_all[NW * NA * code_block_bytes(BITS)];
 
+  // what the epilogue (and the salient product) need per slot and per token, kept here rather than in registers
+  __shared__ __attribute__((aligned(16))) float step_lds[NW][NA][16];
+  __shared__ float2 tok_lds[kTokGroup];
+
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)));
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds);
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -583,69 +646,30 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   ws.template load_code_regs<0>(chunk_at(0));
   ws.template load_code_regs<1>(chunk_at(1));
 
-  // salient fp16 columns: (visit, 32-column block) pairs, dealt round-robin to the column splits, eight pairs
-  // of loads in flight.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
   MES_STAMP(12);
-  f32x4 acc_sal[TT];
-  float sal_scale[TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) { acc_sal[tt] = f32x4{0, 0, 0, 0}; sal_scale[tt] = L.sal_scale[16 * tt + n]; }
-  // What the epilogue needs from memory -- the owning expert's step per output channel and the zero-point
-  // correction per token -- sits behind a pointer that depends on the token's slot.  The pointers are
-  // fetched here, the values after the wait at the end of this start-up phase; they arrive while the
-  // chunks stream.
-  const float* step_ptr[TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) step_ptr[tt] = slot_tok[tt] != 0xffu ? L.step[slot_tok[tt]] : nullptr;
-  if (p.k > 0) {
-    constexpr int SD = 8;
-    const int n_pairs = p.n_vis * p.n_sb;
-    const int mine = (n_pairs - sp + p.nsplit - 1) / p.nsplit;   // pairs sp, sp + nsplit, ...
-    u32x4 sx[SD], sd[SD];
-    int stt[SD];
-    // (visit, block) of the next pair to request, advanced without divisions
-    int rv = 0, rsb = sp, rleft = mine;
-    while (rsb >= p.n_sb) { rsb -= p.n_sb; ++rv; }
-    auto request = [&](u32x4& x, u32x4& d, int& tt_out) {
-      const int info = p.vis_info[rv];
-      tt_out = rleft > 0 ? info >> 8 : -1;
-      x = ld128(reinterpret_cast<const char*>(L.xs) + ((size_t)rv * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
-      d = ld128(L.sal[info & 0xff] + ((size_t)jt * p.n_sb + rsb) * 1024, (uint32_t)lane * 16u);
-      if (rleft > 1) {   // past the last pair the same (valid) pair is requested again and ignored
-        rsb += p.nsplit;
-        while (rsb >= p.n_sb) { rsb -= p.n_sb; ++rv; }
-      }
-      --rleft;
-    };
-    if (mine > 0) {
-#pragma unroll
-      for (int i = 0; i < SD; ++i) request(sx[i], sd[i], stt[i]);
-      for (int i0 = 0; i0 < mine; i0 += SD) {
-#pragma unroll
-        for (int i = 0; i < SD; ++i) {
-#pragma unroll
-          for (int tt = 0; tt < TT; ++tt)
-            if (tt == stt[i]) acc_sal[tt] = mfma_f16(sd[i], sx[i], acc_sal[tt]);
-          request(sx[i], sd[i], stt[i]);
-        }
-      }
-    }
-  }
+  // What the epilogue needs -- every slot's step for this wavefront's 16 output channels, and per token the
+  // zero-point correction and the salient scale -- is fetched now and kept in LDS until then: in registers
+  // it would be live across the whole stream.  (The correction belongs to the whole column range: only the
+  // first split applies it.)
+  const int st_a = lane >> 2, st_j = 16 * jt + 4 * (lane & 3);
+  f32x4 st_v = {0, 0, 0, 0};
+  if (st_a < NA && st_a < p.n_act && st_j < L.d_out) st_v = *reinterpret_cast<const f32x4*>(L.step[st_a] + st_j);
+  float2 tok_v = {0.0f, 0.0f};
+  if (tid < kTokGroup) tok_v = float2{sp == 0 ? L.corr[tid] : 0.0f, L.sal_scale[tid]};
+  ws.sal_begin(sp);
   MES_STAMP(13);
-  // the salient product starts the base accumulators (the scale is an exact power of two)
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) acc_base[tt] = acc_sal[tt] * sal_scale[tt];
+  if (st_a < NA) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
+  if (tid < kTokGroup) tok_lds[tid] = tok_v;
 
   stage_barrier<0>();
-  f32x4 stepv[TT];
-  float corr[TT];
-#pragma unroll
-  for (int tt = 0; tt < TT; ++tt) {
-    const int j = 16 * jt + 4 * g;
-    corr[tt] = sp == 0 ? L.corr[16 * tt + n] : 0.0f;   // belongs to the whole column range: only the first split applies it
-    stepv[tt] = f32x4{0, 0, 0, 0};
-    if (step_ptr[tt] != nullptr && j < L.d_out) stepv[tt] = *reinterpret_cast<const f32x4*>(step_ptr[tt] + j);
+  // Salient pairs beyond what the chunks of this workgroup can carry (short column ranges with many visits)
+  // are multiplied here, one at a time; then the first chunk's pairs are requested.
+  while (ws.sal_left > S::kSalPerChunk * len) {
+    ws.sal_request(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
+    ws.sal_multiply(0);
   }
+#pragma unroll
+  for (int i = 0; i < S::kSalPerChunk; ++i) ws.sal_request(ws.sal_x[i], ws.sal_d[i], ws.sal_tt[i]);
   MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
     ws.template chunk<0>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
@@ -659,9 +683,14 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   f32x4 o[TT];
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt)
+  for (int tt = 0; tt < TT; ++tt) {
+    f32x4 stepv = {0, 0, 0, 0};
+    if (slot_tok[tt] != 0xffu) stepv = *reinterpret_cast<const f32x4*>(&step_lds[wave][slot_tok[tt]][4 * g]);
+    const float2 tk = tok_lds[16 * tt + n];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) o[tt][v] = acc_base[tt][v] + stepv[tt][v] * (acc_raw[tt][v] - corr[tt]);
+    for (int v = 0; v < 4; ++v)
+      o[tt][v] = acc_base[tt][v] + stepv[v] * (acc_raw[tt][v] - tk.x);
+  }
 
   if (p.nsplit > 1) {
     // Split columns: the partial tile goes to the workspace in this kernel's own thread order (fully
@@ -711,32 +740,40 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p)
 // 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
 constexpr int max_pass_slots(int bits) { return bits == 3 ? 10 : 16; }
 
-constexpr int kWaves = 8;   // wavefronts per workgroup; each owns 16 output channels
+// Wavefronts per workgroup (each owns 16 output channels): 8 fill a compute unit's four SIMDs two deep; 7 or 6
+// are chosen when that makes the number of workgroups fit the 256 compute units better.
+constexpr int kMaxWaves = 8;
 
 struct Plan {
   int nsplit;  // workgroups that share one row group's columns
+  int nw;      // wavefronts (row tiles) per workgroup
 };
 
-inline int row_groups_of(int d_out) { return (ceil_to(d_out, kRowPad) / 16 + kWaves - 1) / kWaves; }
+inline int row_groups_of(int d_out, int nw) { return (ceil_to(d_out, kRowPad) / 16 + nw - 1) / nw; }
 
 // Pure function of the shapes (not of bits or T), so the workspace size is known up front.
 // One workgroup runs per compute unit (256 of them).  The chunks are split over `nsplit` workgroups so that
 // the grid fills the largest part of the last round of 256, with at least four chunks per workgroup and,
 // among equals, few splits (every split writes and re-reads a partial output tile).
-Plan plan_for(int d_in, int total_row_groups) {
+Plan plan_for(int d_in, const int* d_out, int n_linears) {
   const int n_chunks = ceil_to(d_in, kColPad) / kChunk;
 #ifdef MES_TRACE
-  if (const char* ov = getenv("MES_PLAN")) { Plan o{1}; if (sscanf(ov, "%d", &o.nsplit) == 1) return o; }
+  if (const char* ov = getenv("MES_PLAN")) { Plan o{1, 8}; if (sscanf(ov, "%d,%d", &o.nsplit, &o.nw) >= 1) return o; }
 #endif
-  Plan best{1};
+  Plan best{1, kMaxWaves};
   double best_cost = 1e30;
-  for (int ns = 1; ns <= 32 && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
-    const long wgs = (long)total_row_groups * ns;
-    const long rounds = (wgs + 255) / 256;
-    const int chunks_wg = (n_chunks + ns - 1) / ns;
-    // time ~ rounds x (chunks per workgroup + a fixed start/finish cost of about three chunks) + the partial tiles
-    const double cost = (double)rounds * (chunks_wg + 3.0) + (ns > 1 ? 0.25 * ns : 0.0);
-    if (cost < best_cost) { best_cost = cost; best = Plan{ns}; }
+  for (int nw = kMaxWaves; nw >= 6; --nw) {
+    int rgs = 0;
+    for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], nw);
+    for (int ns = 1; ns <= 32 && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
+      const long wgs = (long)rgs * ns;
+      const long rounds = (wgs + 255) / 256;
+      const int chunks_wg = (n_chunks + ns - 1) / ns;
+      // time ~ rounds x (chunks per workgroup, each a little shorter with fewer wavefronts, + a fixed start and
+      // finish cost of about three chunks) + the partial tiles
+      const double cost = (double)rounds * (chunks_wg * (nw + 2) / 10.0 + 3.0) + (ns > 1 ? 0.25 * ns : 0.0);
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = Plan{ns, nw}; }
+    }
   }
   return best;
 }
@@ -747,9 +784,9 @@ struct WorkspaceLayout {
 };
 
 WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
+  const Plan pl = plan_for(d_in, d_out, n_linears);
   int rgs = 0;
-  for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l]);
-  const Plan pl = plan_for(d_in, rgs);
+  for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], pl.nw);
   const int pi = ceil_to(d_in, kColPad);
   WorkspaceLayout w;
   size_t off = 0;
@@ -759,25 +796,43 @@ WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
     w.per_linear[l] = off;
     if (l < n_linears) off += w.xs_bytes + 512;
   }
-  w.partial = off; off += pl.nsplit > 1 ? (size_t)rgs * pl.nsplit * 4 * (64 * kWaves) * 16 : 0;
+  w.partial = off; off += pl.nsplit > 1 ? (size_t)rgs * pl.nsplit * 4 * (64 * pl.nw) * 16 : 0;
   w.total = off;
   return w;
 }
 
-template <int BITS, int NA>
+template <int BITS, int NA, int NW>
 hipError_t launch_tt(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
   switch (tt) {
-    case 1: k_delta_linear<BITS, 1, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
-    case 2: k_delta_linear<BITS, 2, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
-    default: k_delta_linear<BITS, 4, NA, kWaves><<<grid, 64 * kWaves, 0, s>>>(p); break;
+    case 1: k_delta_linear<BITS, 1, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
+    case 2: k_delta_linear<BITS, 2, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
+    default: k_delta_linear<BITS, 4, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
   }
   return hipGetLastError();
 }
 
+template <int BITS, int NA>
+hipError_t launch_nw(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
+  switch (nw) {
+    case 6: return launch_tt<BITS, NA, 6>(p, tt, grid, s);
+    case 7: return launch_tt<BITS, NA, 7>(p, tt, grid, s);
+    default: return launch_tt<BITS, NA, 8>(p, tt, grid, s);
+  }
+}
+
 template <int BITS>
-hipError_t launch_na(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
-  if (p.n_act <= 4) return launch_tt<BITS, 4>(p, tt, grid, s);
-  return launch_tt<BITS, max_pass_slots(BITS)>(p, tt, grid, s);
+hipError_t launch_na(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
+  if (p.n_act <= 4) return launch_nw<BITS, 4>(p, tt, nw, grid, s);
+  return launch_nw<BITS, max_pass_slots(BITS)>(p, tt, nw, grid, s);
+}
+
+hipError_t launch_reduce(const LinearParams& p, int tt, int nw, int row_groups, hipStream_t s) {
+  switch (nw) {
+    case 6: k_reduce_splits<6><<<dim3(row_groups, tt), 64 * 6, 0, s>>>(p); break;
+    case 7: k_reduce_splits<7><<<dim3(row_groups, tt), 64 * 7, 0, s>>>(p); break;
+    default: k_reduce_splits<8><<<dim3(row_groups, tt), 64 * 8, 0, s>>>(p); break;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -815,6 +870,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p.k = d0.k;
   p.bits = d0.bits;
   p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
+  const Plan pl = plan_for(d0.d_in, d_outs, c.n_linears);
   int rgs = 0;
   for (int l = 0; l < kMaxLinears; ++l) {
     PerLinear& L = p.lin[l];
@@ -827,10 +883,9 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     L.d_out = d_outs[ll];
     L.n_jt = ceil_to(d_outs[ll], kRowPad) / 16;
     L.rg_begin = rgs;
-    if (l < c.n_linears) rgs += row_groups_of(d_outs[l]);
+    if (l < c.n_linears) rgs += row_groups_of(d_outs[l], pl.nw);
     L.rg_end = rgs;
   }
-  const Plan pl = plan_for(d0.d_in, rgs);
   p.nsplit = pl.nsplit;
   const dim3 grid(rgs, pl.nsplit);
   // Token groups: up to 64 consecutive tokens that belong to at most max_pass_slots experts.
@@ -898,15 +953,14 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     if (e != hipSuccess) return e;
     if (c.ev_start && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
     switch (d0.bits) {
-      case 1: e = launch_na<1>(p, tt, grid, s); break;
-      case 2: e = launch_na<2>(p, tt, grid, s); break;
-      default: e = launch_na<3>(p, tt, grid, s); break;
+      case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
+      case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
+      default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
     }
     if (e != hipSuccess) return e;
     if (c.ev_stop && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;
     if (pl.nsplit > 1) {
-      k_reduce_splits<kWaves><<<dim3(grid.x, tt), 64 * kWaves, 0, s>>>(p);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
+      if ((e = launch_reduce(p, tt, pl.nw, grid.x, s)) != hipSuccess) return e;
     }
     t0 += nt;
   }
