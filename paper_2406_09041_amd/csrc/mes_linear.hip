@@ -433,6 +433,9 @@ struct Stream {
   u32x4 sal_x[kSalPerChunk], sal_d[kSalPerChunk];
   int sal_tt[kSalPerChunk];
   int sal_v, sal_sb, sal_left;   // (visit, block) of the next pair to request; pairs not yet requested
+  bool nx_more;                  // the request being prepared: is there a pair, its visit entry, its addresses
+  int nx_info;
+  const char *nx_xp, *nx_dp;
 
   __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_,
                                     const float2* tok_)
@@ -453,21 +456,29 @@ struct Stream {
     while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
   }
 
-  // Requests the next pair (always two loads, so that the number of loads in flight does not depend on the
-  // data: once the pairs are used up both read the start of the activation stages and tt_out = -1).
-  __device__ __forceinline__ void sal_request(u32x4& x, u32x4& d, int& tt_out) {
-    const bool more = sal_left > 0;
-    const int info = p.vis_info[more ? sal_v : 0];
-    tt_out = more ? info >> 8 : -1;
-    const char* xp = more ? reinterpret_cast<const char*>(L.xs) + ((size_t)sal_v * p.n_sb + sal_sb) * 1024 : p.xt;
-    const char* dp = more ? L.sal[info & 0xff] + ((size_t)jt * p.n_sb + sal_sb) * 1024 : p.xt;
-    x = ld128(xp, (uint32_t)lane * 16u);
-    d = ld128(dp, (uint32_t)lane * 16u);
-    if (more) {
+  // A request is made in three steps spread over a chunk, because its addresses sit behind two dependent
+  // look-ups in the argument tables (visit -> slot -> that expert's salient tile) and a wavefront that
+  // issues in order would otherwise sit out both round trips:  look up the visit;  later form the addresses
+  // and move on to the next pair;  later still issue the loads.
+  __device__ __forceinline__ void sal_lookup() {
+    nx_more = sal_left > 0;
+    nx_info = p.vis_info[nx_more ? sal_v : 0];
+  }
+  __device__ __forceinline__ void sal_address() {
+    nx_xp = nx_more ? reinterpret_cast<const char*>(L.xs) + ((size_t)sal_v * p.n_sb + sal_sb) * 1024 : p.xt;
+    nx_dp = nx_more ? L.sal[nx_info & 0xff] + ((size_t)jt * p.n_sb + sal_sb) * 1024 : p.xt;
+    if (nx_more) {
       --sal_left;
       sal_sb += p.nsplit;
       while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
     }
+  }
+  // Always two loads, so that the number of loads in flight does not depend on the data: once the pairs are
+  // used up both read the start of the activation stages and tt_out = -1.
+  __device__ __forceinline__ void sal_issue(u32x4& x, u32x4& d, int& tt_out) {
+    tt_out = nx_more ? nx_info >> 8 : -1;
+    x = ld128(nx_xp, (uint32_t)lane * 16u);
+    d = ld128(nx_dp, (uint32_t)lane * 16u);
   }
 
   // The pair's 16 x 16 product goes to the base accumulators of its token tile, times the tokens' scale.  Which
@@ -558,6 +569,7 @@ struct Stream {
     MES_CSTAMP(2);
     park<BUF>();
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
+    sal_lookup();
     MES_CSTAMP(3);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
@@ -585,14 +597,13 @@ struct Stream {
         mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
         if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
       } while (++a <= last);
+      if (tt == 0) sal_address();
       MES_CSTAMP(4 + tt);
     }
     // this chunk's salient pairs (requested a chunk ago), and the requests for the next chunk's
-#pragma unroll
-    for (int i = 0; i < kSalPerChunk; ++i) {
-      sal_multiply(i);
-      sal_request(sal_x[i], sal_d[i], sal_tt[i]);
-    }
+    static_assert(kSalPerChunk == 1, "one pair per chunk: the request steps above prepare exactly one");
+    sal_multiply(0);
+    sal_issue(sal_x[0], sal_d[0], sal_tt[0]);
     MES_CSTAMP(8);
     stage_barrier<kYounger>();
     MES_CSTAMP(9);
@@ -665,11 +676,14 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // Salient pairs beyond what the chunks of this workgroup can carry (short column ranges with many visits)
   // are multiplied here, one at a time; then the first chunk's pairs are requested.
   while (ws.sal_left > S::kSalPerChunk * len) {
-    ws.sal_request(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
+    ws.sal_lookup();
+    ws.sal_address();
+    ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
     ws.sal_multiply(0);
   }
-#pragma unroll
-  for (int i = 0; i < S::kSalPerChunk; ++i) ws.sal_request(ws.sal_x[i], ws.sal_d[i], ws.sal_tt[i]);
+  ws.sal_lookup();
+  ws.sal_address();
+  ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
   MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
     ws.template chunk<0>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
