@@ -144,13 +144,15 @@ struct CodeRegs {
 __host__ __device__ constexpr int code_block_bytes(int bits) { return 256 * bits; }
 
 template <int BITS>
+// `blk` is the same in all lanes and the lane offset an unsigned 32-bit number: the load then takes its
+// address as (scalar base) + (vector offset) and needs no 64-bit vector arithmetic.
 __device__ __forceinline__ void load_codes(const char* blk, int lane, CodeRegs<BITS>& r) {
   if constexpr (BITS == 1) {
-    r.lo[0] = *reinterpret_cast<const uint32_t*>(blk + lane * 4);
+    r.lo[0] = *reinterpret_cast<const uint32_t*>(blk + (uint32_t)lane * 4u);
   } else {
-    const u32x2 v = *reinterpret_cast<const u32x2*>(blk + lane * 8);
+    const u32x2 v = *reinterpret_cast<const u32x2*>(blk + (uint32_t)lane * 8u);
     r.lo[0] = v[0]; r.lo[1] = v[1];
-    if constexpr (BITS == 3) r.hi = *reinterpret_cast<const uint32_t*>(blk + 512 + lane * 4);
+    if constexpr (BITS == 3) r.hi = *reinterpret_cast<const uint32_t*>(blk + 512 + (uint32_t)lane * 4u);
   }
 }
 
@@ -386,9 +388,9 @@ __device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, int w
   for (int i = 0; i < (kStageBlocks + NW - 1) / NW; ++i) {
     const int blk = wave + NW * i;
     if (kStageBlocks % NW != 0 && blk >= kStageBlocks) break;   // 32 blocks dealt round-robin: some wavefronts carry one more
-    const char* g = src + blk * 1024 + lane * 16;
+    const char* g = src + blk * 1024;                                 // scalar base; the lanes add 16 * lane
     const uint32_t l = (uint32_t)(uintptr_t)(dst_lds + blk * 1024);   // LDS byte address; the hardware adds 16 * lane
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(g), "s"(l) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"((uint32_t)lane * 16u), "s"(g), "s"(l) : "memory", "m0");
   }
 }
 
@@ -499,9 +501,9 @@ struct Stream {
 
   template <int BUF>
   __device__ __forceinline__ void load_base(int c) {
-    const char* src = L.w_base + ((size_t)c * L.n_jt + jt) * 4096 + lane * 16;
+    const char* src = L.w_base + ((size_t)c * L.n_jt + jt) * 4096;
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
+    for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
   }
 
   template <int BUF>
@@ -542,11 +544,11 @@ struct Stream {
 #pragma unroll
     for (int a = 0; a < NA; ++a)
       if (a * TT / NA == tt) load_codes<BITS>(L.codes[a] + off, lane, code[BUF][a]);
-    const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096 + lane * 16;
+    const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096;
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb)
-      if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = *reinterpret_cast<const u32x4*>(src + kb * 1024);
-    scale[BUF ^ 1][tt] = reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale)[16 * tt + n];
+      if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
+    scale[BUF ^ 1][tt] = *reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale + 64 * tt + (uint32_t)n * 4u);
   }
 
   __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
@@ -627,15 +629,18 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
   MES_STAMP(0);
 
-  // two stages, as two arrays: a copy into one never touches what is read from the other
-  __shared__ __attribute__((aligned(16))) char stage0[kStageLds];
-  __shared__ __attribute__((aligned(16))) char stage1[kStageLds];
-  // parked code words: one private area per wavefront
-  __shared__ __attribute__((aligned(16))) char park_all[NW * NA * code_block_bytes(BITS)];
-
-  // what the epilogue (and the salient product) need per slot and per token, kept here rather than in registers
-  __shared__ __attribute__((aligned(16))) float step_lds[NW][NA][16];
-  __shared__ float2 tok_lds[kTokGroup];
+  // One LDS block carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
+  // offset field of the LDS instructions, so one lane-offset register serves every operand read.
+  //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | parked code words, one private area per wavefront |
+  //   per wavefront and slot the 16 steps | per token (correction, salient scale)
+  constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
+  constexpr int kStepBytes = NW * NA * 16 * 4;
+  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8];
+  char* const stage0 = lds;
+  char* const stage1 = lds + kStageLds;
+  char* const park_all = lds + 2 * kStageLds;
+  float (*step_lds)[NA][16] = reinterpret_cast<float (*)[NA][16]>(lds + 2 * kStageLds + kParkBytes);
+  float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
 
   using S = Stream<BITS, TT, NA, NW>;
   S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds);
