@@ -573,20 +573,21 @@ struct Stream {
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
     sal_lookup();
     MES_CSTAMP(3);
+    // Order inside a tile: the low-bit visits first (operands bhi / blo, read from LDS during the previous
+    // tile's base product), then the base product (operands xb, read while the visits ran).  Every LDS read is
+    // thereby issued a good stretch of arithmetic before its data are needed.
+    v8i bhi = lds_fp8(cur, 0, 0, lane), blo = lds_fp8(cur, 0, 1, lane);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       // this tile's share of the next chunks' requests: spreading them over the chunk keeps the memory
       // pipeline fed without ever asking it to take a whole chunk's loads at once (which blocks the
       // wavefront, and with it the arithmetic it could be doing, until the pipeline has room)
       request_share<BUF>(tt, cn, c2);
-      const v8i bhi = lds_fp8(cur, tt, 0, lane), blo = lds_fp8(cur, tt, 1, lane);
       const int first = p.tile_first[tt], last = p.tile_last[tt];
       CodeRegs<BITS> cr = parked(first);
       u32x4 xb[4];
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
       // every tile of the launch has at least one visit (the host gives an empty tile slot 0, whose tokens
       // are nobody's: scale 0), so there is no branch around the loop and no second copy of the accumulator
       int a = first;
@@ -599,10 +600,12 @@ struct Stream {
         mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
         if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
       } while (++a <= last);
+      if (tt + 1 < TT) { bhi = lds_fp8(cur, tt + 1, 0, lane); blo = lds_fp8(cur, tt + 1, 1, lane); }
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
       if (tt == 0) sal_address();
       MES_CSTAMP(4 + tt);
     }
-    // this chunk's salient pairs (requested a chunk ago), and the requests for the next chunk's
     static_assert(kSalPerChunk == 1, "one pair per chunk: the request steps above prepare exactly one");
     sal_multiply(0);
     sal_issue(sal_x[0], sal_d[0], sal_tt[0]);
