@@ -205,8 +205,9 @@ __device__ __forceinline__ uint32_t to_e4m3_rtz(float v, float& back) {
   return byte | (sign << 7);
 }
 
-// Block roles by blockIdx.x: [0, n_chunks) build one chunk's stage; [n_chunks, n_chunks + n_vis) gather one
-// visit's salient activations; then 64 blocks, one per token, for the per-token correction.  256 threads.
+// Block roles by blockIdx.x: [0, 4 n_chunks) build one token tile of one chunk's stage; then per linear n_vis
+// blocks that gather one visit's salient activations and 64 blocks, one per token, for the per-token
+// correction.  256 threads.
 //
 // Stage of chunk c (what the main kernel copies to LDS), columns counted from 128 c, lane = 16 g + n:
 //   bytes [0, 16384)      bf16, [kb][tt][lane][8]: x[16 tt + n][32 kb + 8 g + 0..7]
@@ -215,74 +216,57 @@ __device__ __forceinline__ uint32_t to_e4m3_rtz(float v, float& back) {
 //   bytes [32768, 33024)  int32 [64]: 128 + s of token 16 tt + n, i.e. the scale byte 2^(s+1) (the extra
 //                         factor two undoes the fp4 codes' u / 2)
 __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
-  const int b = blockIdx.x, tid = threadIdx.x;
-  if (b < p.n_chunks) {
-    char* stage = p.xt + (size_t)b * kStageBytes;
-    // bf16 tiles: 1024 slots, four per thread
+  const int tid = threadIdx.x;
+  int b = blockIdx.x;
+  if (b < 4 * p.n_chunks) {
+    // (chunk c, token tile tt): thread = (token n of the tile, 8 columns `part` of the chunk's 128)
+    const int c = b >> 2, tt = b & 3;
+    if (p.t0 + 16 * tt >= p.T) return;   // a tile past the last token: the main kernel never reads it
+    char* stage = p.xt + (size_t)c * kStageBytes;
+    const int n = tid >> 4, part = tid & 15, q = part >> 2, i = part & 3;
+    const int t = p.t0 + 16 * tt + n, col = kChunk * c + 8 * part;
+    u32x4 v = {0, 0, 0, 0};
+    if (t < p.T && col < p.d_in) v = *reinterpret_cast<const u32x4*>(p.x + (size_t)t * p.d_in + col);
+    // bf16 image: these eight columns are lane 16 i + n of block (kb = q, tt)
+    *reinterpret_cast<u32x4*>(stage + ((q * 4 + tt) * 64 + 16 * i + n) * 16) = v;
+    float xv[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int s = tid + 256 * i;
-      const int lane = s & 63, tt = (s >> 6) & 3, kb = s >> 8;
-      const int t = p.t0 + 16 * tt + (lane & 15), col = kChunk * b + 32 * kb + 8 * (lane >> 4);
-      u32x4 v = {0, 0, 0, 0};
-      if (t < p.T && col < p.d_in) v = *reinterpret_cast<const u32x4*>(p.x + (size_t)t * p.d_in + col);
-      *reinterpret_cast<u32x4*>(stage + s * 16) = v;
+    for (int e = 0; e < 4; ++e) {
+      xv[2 * e] = bf16_to_f32((uint16_t)(v[e] & 0xffffu));
+      xv[2 * e + 1] = bf16_to_f32((uint16_t)(v[e] >> 16));
     }
-    // fp8 pieces: thread (token tl, quarter q) owns columns 32 q .. 32 q + 31 of the chunk
-    const int tl = tid >> 2, q = tid & 3;
-    const int t = p.t0 + tl;
-    float xv[32];
     float amax = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int col = kChunk * b + 32 * q + 8 * i;
-      u32x4 v = {0, 0, 0, 0};
-      if (t < p.T && col < p.d_in) v = *reinterpret_cast<const u32x4*>(p.x + (size_t)t * p.d_in + col);
+    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xv[e]));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        xv[8 * i + 2 * e] = bf16_to_f32((uint16_t)(v[e] & 0xffffu));
-        xv[8 * i + 2 * e + 1] = bf16_to_f32((uint16_t)(v[e] >> 16));
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(xv[i]));
-    amax = fmaxf(amax, __shfl_xor(amax, 1));
-    amax = fmaxf(amax, __shfl_xor(amax, 2));
+    for (int off = 1; off < 16; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));   // the token's 16 threads
     // s = exponent(amax) - 7 puts the largest scaled value in [128, 256); clamped so that 128 + s is a
     // valid scale byte.  Non-finite activations give non-finite outputs either way.
     int s = (int)((__float_as_uint(amax) >> 23) & 0xffu) - 127 - 7;
     if (amax == 0.0f) s = 0;
     s = s < -126 ? -126 : (s > 120 ? 120 : s);
     const float inv = __uint_as_float((uint32_t)(127 - s) << 23);   // 2^-s
-    uint32_t hib[8], lob[8];
+    uint32_t hw[2] = {0, 0}, lw[2] = {0, 0};
 #pragma unroll
-    for (int w = 0; w < 8; ++w) {
-      uint32_t hw = 0, lw = 0;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float v = xv[4 * w + e] * inv;
-        float hv, lv;
-        const uint32_t hb = to_e4m3_rtz(v, hv);
-        const uint32_t lb = to_e4m3_rtz(v - hv, lv);
-        hw |= hb << (8 * e);
-        lw |= lb << (8 * e);
-      }
-      hib[w] = hw; lob[w] = lw;
+    for (int e = 0; e < 8; ++e) {
+      const float sv = xv[e] * inv;
+      float hv, lv;
+      const uint32_t hb = to_e4m3_rtz(sv, hv);
+      const uint32_t lb = to_e4m3_rtz(sv - hv, lv);
+      hw[e >> 2] |= hb << (8 * (e & 3));
+      lw[e >> 2] |= lb << (8 * (e & 3));
     }
-    // columns 32 q + 16 j + e  ->  half = q / 2, lane group g = 2 (q % 2) + j, byte e
-    const int tt = tl >> 4, n = tl & 15, half = q >> 1;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int lane = 16 * (2 * (q & 1) + j) + n;
-      char* dst = stage + kStageFp8 + ((tt * 2 + 0) * 2 + half) * 1024 + lane * 16;
-      *reinterpret_cast<u32x4*>(dst) = u32x4{hib[4 * j], hib[4 * j + 1], hib[4 * j + 2], hib[4 * j + 3]};
-      *reinterpret_cast<u32x4*>(dst + 2048) = u32x4{lob[4 * j], lob[4 * j + 1], lob[4 * j + 2], lob[4 * j + 3]};
-    }
-    if (q == 0) *reinterpret_cast<int*>(stage + kStageScale + tl * 4) = 128 + s;
+    // columns 32 q + 8 i + e  ->  half = q / 2, lane group g = 2 (q % 2) + i / 2, bytes 8 (i % 2) + e
+    const int lane = 16 * (2 * (q & 1) + (i >> 1)) + n;
+    char* dst = stage + kStageFp8 + ((tt * 2 + 0) * 2 + (q >> 1)) * 1024 + lane * 16 + 8 * (i & 1);
+    *reinterpret_cast<u32x2*>(dst) = u32x2{hw[0], hw[1]};
+    *reinterpret_cast<u32x2*>(dst + 2048) = u32x2{lw[0], lw[1]};
+    if (part == 0) *reinterpret_cast<int*>(stage + kStageScale + (16 * tt + n) * 4) = 128 + s;
     return;
   }
+  b -= 4 * p.n_chunks;
   const int per_linear = p.n_vis + kTokGroup;
-  const int li = (b - p.n_chunks) / per_linear, role = (b - p.n_chunks) - li * per_linear;
+  const int li = b / per_linear, role = b - li * per_linear;
   const PerLinear& L = p.lin[li];
   if (role < p.n_vis) {
     // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
@@ -298,10 +282,41 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     const int tl = 16 * tt + n;
     const bool inm = tl >= p.lo[a] && tl < p.hi[a];
     const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
+    // Item i = (32-column block sb = i / 64, lane = i % 64) is one B-operand register set: eight gathered
+    // activations.  Up to kItems items per thread are gathered once and kept in registers across the
+    // per-token maximum (k <= 512); beyond that the values are gathered a second time.
+    constexpr int kItems = 4;
+    const int n_items = p.n_sb * 64;
+    const bool in_regs = n_items <= 256 * kItems;
+    uint32_t raw[kItems][4];   // two bf16 per word, as gathered
+    auto gather = [&](int i, uint32_t (&w)[4]) {
+      const int sb = i >> 6, gg = (i & 63) >> 4;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r0 = 32 * sb + 8 * gg + 2 * q;   // indices are clamped so that a corrupt list can never address outside the row
+        uint32_t v0 = 0, v1 = 0;
+        if (inm && r0 < p.k) v0 = xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))];
+        if (inm && r0 + 1 < p.k) v1 = xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))];
+        w[q] = v0 | (v1 << 16);
+      }
+    };
     uint32_t mymax = 0;
-    if (inm)
-      for (int r = tid >> 4; r < p.k; r += 16)   // indices are clamped so that a corrupt list can never address outside the row
+    if (in_regs) {
+#pragma unroll
+      for (int j = 0; j < kItems; ++j) {
+        const int i = tid + 256 * j;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) raw[j][q] = 0;
+        if (i < n_items) {
+          gather(i, raw[j]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) mymax = max(mymax, max(raw[j][q] & 0x7fffu, (raw[j][q] >> 16) & 0x7fffu));
+        }
+      }
+    } else if (inm) {
+      for (int r = tid >> 4; r < p.k; r += 16)
         mymax = max(mymax, (uint32_t)(xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))] & 0x7fffu));
+    }
     if (mymax) atomicMax(&smax[tid & 15], mymax);   // (tid & 15) == n: the same token
     __syncthreads();
     int e = (int)(smax[n] >> 7) - 127 - 14;          // bf16 exponent field of the largest magnitude
@@ -309,28 +324,40 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     e = e < -110 ? -110 : (e > 110 ? 110 : e);
     const float inv = __uint_as_float((uint32_t)(127 - e) << 23);
     if (inm && tid < 16) L.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
-    for (int i = tid; i < p.n_sb * 64; i += 256) {
-      const int sb = i >> 6;
+    auto convert_store = [&](int i, const uint32_t (&w)[4]) {
       u32x4 o;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int r0 = 32 * sb + 8 * g + 2 * q;
-        float v0 = 0.0f, v1 = 0.0f;
-        if (inm && r0 < p.k) v0 = bf16_to_f32(xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))]) * inv;
-        if (inm && r0 + 1 < p.k) v1 = bf16_to_f32(xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))]) * inv;
+        const float v0 = bf16_to_f32((uint16_t)(w[q] & 0xffffu)) * inv, v1 = bf16_to_f32((uint16_t)(w[q] >> 16)) * inv;
         o[q] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v0) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v1) << 16);
       }
-      L.xs[((size_t)v * p.n_sb + sb) * 64 + lane] = o;
+      L.xs[((size_t)v * p.n_sb + (i >> 6)) * 64 + (i & 63)] = o;
+    };
+    if (in_regs) {
+#pragma unroll
+      for (int j = 0; j < kItems; ++j)
+        if (tid + 256 * j < n_items) convert_store(tid + 256 * j, raw[j]);
+    } else {
+      for (int i = tid; i < n_items; i += 256) {
+        uint32_t w[4];
+        gather(i, w);
+        convert_store(i, w);
+      }
     }
     return;
   }
   // per-token correction  z (sum_i x_i - sum_{salient} x_i)
   const int tl = role - p.n_vis;
   const int t = p.t0 + tl;
-  __shared__ double red[256];
+  __shared__ double red[4];
   double acc = 0.0;
   if (t < p.T) {
     const uint16_t* xrow = p.x + (size_t)t * p.d_in;
+    // the salient indices first: the gather below waits for them, the row sum does not
+    const int a = p.tok_slot[tl];
+    const int32_t* si = a != 0xff ? L.sidx[a] : nullptr;
+    int idx0 = -1;
+    if (si != nullptr && tid < p.k) idx0 = (int)min((uint32_t)si[tid], (uint32_t)(p.d_in - 1));
     for (int c8 = tid; c8 < p.d_in / 8; c8 += 256) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(xrow + 8 * c8);
       float part = 0.0f;
@@ -338,18 +365,17 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
       for (int q = 0; q < 4; ++q) part += bf16_to_f32((uint16_t)(v[q] & 0xffffu)) + bf16_to_f32((uint16_t)(v[q] >> 16));
       acc += (double)part;
     }
-    const int a = p.tok_slot[tl];
-    if (a != 0xff)
-      for (int r = tid; r < p.k; r += 256)
-        acc -= (double)bf16_to_f32(xrow[min((uint32_t)L.sidx[a][r], (uint32_t)(p.d_in - 1))]);
+    if (idx0 >= 0) acc -= (double)bf16_to_f32(xrow[idx0]);
+    if (si != nullptr)
+      for (int r = tid + 256; r < p.k; r += 256)
+        acc -= (double)bf16_to_f32(xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))]);
   }
-  red[tid] = acc;
+  // sum over the 256 threads: inside each wavefront by lane exchange, then the four wavefront sums
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if ((tid & 63) == 0) red[tid >> 6] = acc;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) red[tid] += red[tid + s];
-    __syncthreads();
-  }
-  if (tid == 0) L.corr[tl] = (float)((double)p.z * red[0]);
+  if (tid == 0) L.corr[tl] = (float)((double)p.z * (((red[0] + red[1]) + red[2]) + red[3]));
 }
 
 // ---- main kernel ------------------------------------------------------------------------------------
@@ -970,7 +996,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
     p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
-    k_prepare<<<p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
+    k_prepare<<<4 * p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (c.ev_start && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
