@@ -446,6 +446,12 @@ struct Stream {
   const LinearParams& p;
   const PerLinear& L;
   int lane, n, jt;
+  // The wavefront's tile tt (a compile-time index: it names accumulators) is token tile pt(tt) of the launch:
+  // the same, or the mirror image for the second wavefront of each SIMD.  The two then run through the tiles
+  // in opposite orders, so that the tile with many visits (long runs of matrix instructions) of one falls on
+  // the tiles with few of the other instead of both queueing for the matrix pipeline at the same time.
+  int rev;
+  __device__ __forceinline__ int pt(int tt) const { return rev ? TT - 1 - tt : tt; }
   char* parkp;                // this wavefront's LDS area: [NA][kSlotLds]
   uint32_t slot_tok[TT];
   int scale[2][TT];           // per-token block scales of the current / next chunk
@@ -466,11 +472,11 @@ struct Stream {
   const char *nx_xp, *nx_dp;
 
   __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_,
-                                    const float2* tok_)
-      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), parkp(park_), tok(tok_) {
+                                    const float2* tok_, int rev_)
+      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), rev(rev_), parkp(park_), tok(tok_) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      slot_tok[tt] = p.tok_slot[16 * tt + n];
+      slot_tok[tt] = p.tok_slot[16 * pt(tt) + n];
       acc_base[tt] = f32x4{0, 0, 0, 0};
       acc_raw[tt] = f32x4{0, 0, 0, 0};
     }
@@ -519,7 +525,7 @@ struct Stream {
     const float ss = stt >= 0 ? tok[16 * (stt >= 0 ? stt : 0) + n].y : 0.0f;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      const float m = tt == stt ? ss : 0.0f;
+      const float m = pt(tt) == stt ? ss : 0.0f;
 #pragma unroll
       for (int v = 0; v < 4; ++v) acc_base[tt][v] += t[v] * m;
     }
@@ -536,7 +542,7 @@ struct Stream {
   __device__ __forceinline__ void load_scales(int c) {
     const int* src = reinterpret_cast<const int*>(p.xt + (size_t)c * kStageBytes + kStageScale);
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = src[16 * tt + n];
+    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = src[16 * pt(tt) + n];
   }
 
   template <int BUF>
@@ -574,7 +580,7 @@ struct Stream {
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb)
       if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
-    scale[BUF ^ 1][tt] = *reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale + 64 * tt + (uint32_t)n * 4u);
+    scale[BUF ^ 1][tt] = *reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale + 64 * pt(tt) + (uint32_t)n * 4u);
   }
 
   __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
@@ -602,18 +608,18 @@ struct Stream {
     // Order inside a tile: the low-bit visits first (operands bhi / blo, read from LDS during the previous
     // tile's base product), then the base product (operands xb, read while the visits ran).  Every LDS read is
     // thereby issued a good stretch of arithmetic before its data are needed.
-    v8i bhi = lds_fp8(cur, 0, 0, lane), blo = lds_fp8(cur, 0, 1, lane);
+    v8i bhi = lds_fp8(cur, pt(0), 0, lane), blo = lds_fp8(cur, pt(0), 1, lane);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       // this tile's share of the next chunks' requests: spreading them over the chunk keeps the memory
       // pipeline fed without ever asking it to take a whole chunk's loads at once (which blocks the
       // wavefront, and with it the arithmetic it could be doing, until the pipeline has room)
       request_share<BUF>(tt, cn, c2);
-      const int first = p.tile_first[tt], last = p.tile_last[tt];
+      const int first = p.tile_first[pt(tt)], last = p.tile_last[pt(tt)];
       CodeRegs<BITS> cr = parked(first);
       u32x4 xb[4];
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + tt) * 1024 + lane * 16);
+      for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + pt(tt)) * 1024 + lane * 16);
       // every tile of the launch has at least one visit (the host gives an empty tile slot 0, whose tokens
       // are nobody's: scale 0), so there is no branch around the loop and no second copy of the accumulator
       int a = first;
@@ -626,7 +632,7 @@ struct Stream {
         mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
         if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
       } while (++a <= last);
-      if (tt + 1 < TT) { bhi = lds_fp8(cur, tt + 1, 0, lane); blo = lds_fp8(cur, tt + 1, 1, lane); }
+      if (tt + 1 < TT) { bhi = lds_fp8(cur, pt(tt + 1), 0, lane); blo = lds_fp8(cur, pt(tt + 1), 1, lane); }
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
       if (tt == 0) sal_address();
@@ -672,7 +678,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
 
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds);
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -734,7 +740,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   for (int tt = 0; tt < TT; ++tt) {
     f32x4 stepv = {0, 0, 0, 0};
     if (slot_tok[tt] != 0xffu) stepv = *reinterpret_cast<const f32x4*>(&step_lds[wave][slot_tok[tt]][4 * g]);
-    const float2 tk = tok_lds[16 * tt + n];
+    const float2 tk = tok_lds[16 * ws.pt(tt) + n];
 #pragma unroll
     for (int v = 0; v < 4; ++v)
       o[tt][v] = acc_base[tt][v] + stepv[v] * (acc_raw[tt][v] - tk.x);
@@ -746,13 +752,13 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
     constexpr int NT = 64 * NW;
     f32x4* part = p.partial + ((size_t)rg * p.nsplit + sp) * (4 * NT);
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) part[tt * NT + tid] = o[tt];
+    for (int tt = 0; tt < TT; ++tt) part[ws.pt(tt) * NT + tid] = o[tt];
     return;
   }
   if (!live) return;
 #pragma unroll
   for (int tt = 0; tt < TT; ++tt) {
-    const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
+    const int t = p.t0 + 16 * ws.pt(tt) + n, j = 16 * jt + 4 * g;
     if (t < p.T && j < L.d_out) {
       uint2 pk;
       pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
