@@ -601,7 +601,6 @@ struct Stream {
 #define MES_CSTAMP(i) do { } while (0)
 #endif
     MES_CSTAMP(2);
-    park<BUF>();
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
     sal_lookup();
     MES_CSTAMP(3);
@@ -641,6 +640,10 @@ struct Stream {
     static_assert(kSalPerChunk == 1, "one pair per chunk: the request steps above prepare exactly one");
     sal_multiply(0);
     sal_issue(sal_x[0], sal_d[0], sal_tt[0]);
+    // The next chunk's code words (requested during the previous chunk) go to this wavefront's LDS area now:
+    // its visits of this chunk are over, the area is its own, and the wavefronts get here at slightly
+    // different times -- the 64 KiB of LDS writes spread out and fill what would be waiting at the barrier.
+    park<BUF ^ 1>();
     MES_CSTAMP(8);
     stage_barrier<kYounger>();
     MES_CSTAMP(9);
@@ -712,6 +715,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   if (st_a < NA) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
   if (tid < kTokGroup) tok_lds[tid] = tok_v;
 
+  ws.template park<0>();
   stage_barrier<0>();
   // Salient pairs beyond what the chunks of this workgroup can carry (short column ranges with many visits)
   // are multiplied here, one at a time; then the first chunk's pairs are requested.
