@@ -673,12 +673,13 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   //   per wavefront and slot the 16 steps | per token (correction, salient scale)
   constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
   constexpr int kStepBytes = NW * NA * 16 * 4;
-  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8];
+  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + 256];
   char* const stage0 = lds;
   char* const stage1 = lds + kStageLds;
   char* const park_all = lds + 2 * kStageLds;
   float (*step_lds)[NA][16] = reinterpret_cast<float (*)[NA][16]>(lds + 2 * kStageLds + kParkBytes);
   float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
+  char* const warm_lds = lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8;   // 256 bytes nobody reads
 
   using S = Stream<BITS, TT, NA, NW>;
   S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
@@ -693,6 +694,22 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int len = c_end - c_begin;
   const int rot = ((rg & 7) * len) >> 3;
   auto chunk_at = [&](int i) { i = i < len ? i : len - 1; int r = i + rot; r = r >= len ? r - len : r; return c_begin + r; };
+  // Address translation warm-up.  The first loads of a workgroup go to as many pages as there are experts, and
+  // a wavefront issues in order: left alone, each would sit out one translation miss after the other (about
+  // 0.1 us each, 3 us for 32 code-word loads).  Instead the wavefronts split the (slot, chunk) combinations among
+  // themselves and touch each page once with a 4-byte LDS-DMA load (no destination register to keep track
+  // of), all in parallel; the real loads below then find their translations cached.
+  {
+    constexpr int kCombos = 2 * NA, kPer = (kCombos + NW - 1) / NW;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      const int combo = (wave * kPer + i) % kCombos;
+      const int a = combo >> 1;
+      const char* g = L.codes[a < p.n_act ? a : 0] + ((size_t)chunk_at(combo & 1) * L.n_jt + jt) * code_block_bytes(BITS);
+      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                   : : "v"((uint32_t)lane * 4u), "s"(g), "s"((uint32_t)(uintptr_t)warm_lds) : "memory", "m0");
+    }
+  }
   // first chunks' activations and weights: requested now, needed after the salient product below
   stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
   ws.template load_base<0>(chunk_at(0));
