@@ -106,7 +106,7 @@ def quantize(delta32: np.ndarray, salient_idx, bits: int, grid: int = GRID_SYM,
       salient fp16  [d_out, k]:    delta[:, salient_idx] rounded to fp16 (RNE)
     """
     assert delta32.dtype == np.float32 and delta32.ndim == 2
-    if bits not in (1, 2, 3):
+    if bits not in (1, 2, 3, 4):
         raise ValueError("bits")
     if grid == GRID_EQ1 and bits == 1:
         raise ValueError("Eq. 1 is undefined for b = 1")
@@ -304,8 +304,9 @@ def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
     Blocks of 16 rows x 128 columns, chunk-major (all row tiles of one 128-column chunk are contiguous).
     Lane 16 g + r owns row 16 jt + r and the 32 columns 128 c + 32 g + 8 q + p.  b = 1: one word per lane,
     code at bit 4 p + q.  b = 2: words [lane][w], code of (q, p) in word q // 2 at bits 4 p + 2 (q % 2).
-    b = 3: the b = 2 block of the low two bits, then the b = 1 block of the high bit.  Salient columns,
-    padding columns and padding rows store code 0.
+    b = 3: the b = 2 block of the low two bits, then the b = 1 block of the high bit.  b = 4: the b = 2 block of
+    the low two bits, then the b = 2 block of the high two bits.  Salient columns, padding columns and padding
+    rows store code 0.
     """
     d_out, d_in = codes.shape
     po, pi, _ = padded_dims(d_out, d_in)
@@ -321,7 +322,10 @@ def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
     low = _nibble_words(v & np.uint32(3), 2).reshape(pi // 128, po // 16, 128)
     if bits == 2:
         return low
-    high = _nibble_words(v >> np.uint32(2), 1).reshape(pi // 128, po // 16, 64)
+    if bits == 3:
+        high = _nibble_words(v >> np.uint32(2), 1).reshape(pi // 128, po // 16, 64)
+    else:
+        high = _nibble_words(v >> np.uint32(2), 2).reshape(pi // 128, po // 16, 128)
     return np.concatenate([low, high], axis=2)
 
 
@@ -334,6 +338,8 @@ def unpack_codes(packed: np.ndarray, bits: int, d_out: int, d_in: int) -> np.nda
         v = _unnibble_words(packed[:, :, :128].reshape(nc, njt, 64, 2), 2)
         if bits == 3:
             v = v | (_unnibble_words(packed[:, :, 128:].reshape(nc, njt, 64, 1), 1) << np.uint32(2))
+        if bits == 4:
+            v = v | (_unnibble_words(packed[:, :, 128:].reshape(nc, njt, 64, 2), 2) << np.uint32(2))
     v = v.reshape(nc, njt, 4, 16, 4, 8).transpose(1, 3, 0, 2, 4, 5)   # jt, r, c, g, q, p
     return np.ascontiguousarray(v).reshape(njt * 16, nc * 128)[:d_out, :d_in].astype(np.uint8)
 

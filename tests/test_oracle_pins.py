@@ -28,7 +28,7 @@ def _delta(d_out, d_in, seed, k=0, scale=15.0):
 
 # ---------------------------------------------------------------- pack / unpack round trip
 
-@pytest.mark.parametrize("bits", [1, 2, 3])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 @pytest.mark.parametrize("shape", [(16, 64), (70, 248), (33, 515), (1, 1), (64, 1031)])
 def test_pack_unpack_roundtrip(bits, shape):
     d_out, d_in = shape
@@ -40,7 +40,7 @@ def test_pack_unpack_roundtrip(bits, shape):
     assert np.array_equal(back, codes)
 
 
-@pytest.mark.parametrize("bits", [1, 2, 3])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_pack_every_bit_is_used_exactly_once(bits):
     """One-hot probes: each (row, column, code bit) lands on its own bit of the packed words, none collide,
     and the place is the one the layout specification gives."""
@@ -63,6 +63,8 @@ def test_pack_every_bit_is_used_exactly_once(bits):
                 if bits == 1 or (bits == 3 and cb == 2):         # one word per lane, bit 4 p + q
                     off = 128 if bits == 3 else 0
                     assert (widx, bit) == (off + lane, 4 * p + q)
+                elif bits == 4 and cb >= 2:                      # the second 2-bit block: the high two bits
+                    assert (widx, bit) == (128 + 2 * lane + q // 2, 4 * p + 2 * (q % 2) + cb - 2)
                 else:                                            # two words per lane, 2-bit fields
                     assert (widx, bit) == (2 * lane + q // 2, 4 * p + 2 * (q % 2) + cb)
                 assert (row // 16, widx, bit) not in seen
@@ -100,6 +102,18 @@ def test_packed_words_are_fp4_operands():
             for p in range(8):
                 u = int(codes[row, 32 * g + 8 * q + p])
                 assert e2m1((lo_reg >> (4 * p)) & 15) + e2m1((hi_reg >> (4 * p)) & 15) == u / 2
+    # b = 4: two 2-bit planes; the high plane counts four times (a block scale of 2^2 in the kernel)
+    codes = _rng(10).integers(0, 16, size=(16, 128), dtype=np.uint8)
+    packed = O.pack_codes(codes, 4)[0, 0]
+    low, high = packed[:128].reshape(64, 2), packed[128:].reshape(64, 2)
+    for lane in (3, 30, 62):
+        row, g = lane % 16, lane // 16
+        for q in range(4):
+            lo_reg = (int(low[lane, q // 2]) >> (2 * (q % 2))) & 0x33333333
+            hi_reg = (int(high[lane, q // 2]) >> (2 * (q % 2))) & 0x33333333
+            for p in range(8):
+                u = int(codes[row, 32 * g + 8 * q + p])
+                assert e2m1((lo_reg >> (4 * p)) & 15) + 4 * e2m1((hi_reg >> (4 * p)) & 15) == u / 2
 
 
 def test_pack_padding_and_salient_are_zero_codes():
@@ -133,8 +147,8 @@ def test_base_and_salient_tiling_roundtrip_and_slot_rule():
 
 # ---------------------------------------------------------------- Eq. 1: quantiser
 
-@pytest.mark.parametrize("bits,grid", [(1, O.GRID_SYM), (2, O.GRID_SYM), (3, O.GRID_SYM),
-                                       (2, O.GRID_EQ1), (3, O.GRID_EQ1)])
+@pytest.mark.parametrize("bits,grid", [(1, O.GRID_SYM), (2, O.GRID_SYM), (3, O.GRID_SYM), (4, O.GRID_SYM),
+                                       (2, O.GRID_EQ1), (3, O.GRID_EQ1), (4, O.GRID_EQ1)])
 def test_rounding_error_at_most_half_a_step(bits, grid):
     """With the initial step nothing clips, so |w - w_hat| <= s/2 everywhere (Eq. 1)."""
     delta, sidx = _delta(48, 300, bits + 10 * grid, k=8)
@@ -148,7 +162,7 @@ def test_rounding_error_at_most_half_a_step(bits, grid):
     assert codes[:, ns].max() == 2 ** bits - 1 and codes[:, ns].min() == 0 or grid == O.GRID_EQ1
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_eq1_level_set(bits):
     """Eq. 1: integer levels -2^(b-1) .. 2^(b-1)-1; with s = max|X|/(2^(b-1)-1) the row maximum sits on +Q_P."""
     delta, _ = _delta(32, 200, 77 + bits)
@@ -243,7 +257,7 @@ def test_invalid_arguments():
     with pytest.raises(ValueError):
         O.quantize(delta, [], 1, O.GRID_EQ1)
     with pytest.raises(ValueError):
-        O.quantize(delta, [], 4)
+        O.quantize(delta, [], 5)
     with pytest.raises(ValueError):
         O.quantize(delta, [], 2, O.GRID_SYM, O.STEP_MEANABS)
 
