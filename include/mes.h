@@ -4,7 +4,7 @@
  * The operation is the serving hot path of ME-Switch (arXiv 2406.09041): every
  * expert's weight is the shared pre-trained W_base plus a delta (Section 3,
  * "delta = W_FT - W").  The delta's non-salient input channels are quantised to
- * b = 1..3 bits with one step size per output channel (Eq. 1, Section 4.1), its k
+ * b = 1..4 bits with one step size per output channel (Eq. 1, Section 4.1), its k
  * salient input channels stay in fp16 (Section 4.1, "Salient-aware delta
  * selection", Eq. 2), and inference is decoupled as y = x W + x Delta~ (Eq. 4),
  * batched across experts.
@@ -44,6 +44,8 @@
  *                      bits [4 p + 2 (q % 2), + 2).
  *               b = 3: the b = 2 block holding the low two code bits (512 bytes), followed
  *                      by a b = 1 block holding the high code bit (256 bytes).
+ *               b = 4: the b = 2 block holding the low two code bits (512 bytes), followed
+ *                      by a b = 2 block holding the high two code bits (512 bytes).
  *             Codes of salient columns, padding columns and padding rows are 0.
  *    The code u is unsigned; the weight it stands for is (u - z) * step[row] with
  *    z = 2^(b-1) - 1/2 (MES_GRID_SYM) or 2^(b-1) (MES_GRID_EQ1, Eq. 1's levels).
@@ -62,7 +64,7 @@ typedef enum {
   MES_OK = 0,
   MES_ERR_NULL = 1,      /* a required pointer is NULL                               */
   MES_ERR_SHAPE = 2,     /* non-positive / unsupported / mismatching dimensions      */
-  MES_ERR_BITS = 3,      /* bits not in {1,2,3}, or a grid/step policy it excludes   */
+  MES_ERR_BITS = 3,      /* bits not in {1,2,3,4}, or a grid/step policy it excludes   */
   MES_ERR_SALIENT = 4,   /* k out of range, or salient_idx not ascending / in range  */
   MES_ERR_SEGMENTS = 5,  /* seg_offsets not 0 = o[0] <= ... <= o[E] = T              */
   MES_ERR_ALIGN = 6,     /* a pointer is not 16-byte aligned                         */
@@ -178,8 +180,10 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
 
 /* Measurement hook (for benchmarks; the latency analysis of Section 5.2 times the layer, this times its dominant
  * kernel): the NEXT mes_delta_linear / mes_delta_linear_multi call of the calling thread records `start_event`
- * on its stream immediately before its streaming kernel and `stop_event` immediately after it (hipEvent_t
- * passed as void*, HOST handles owned by the caller; with more than one token group the last group's).
+ * on its stream immediately before its first streaming kernel and `stop_event` immediately after its last one
+ * (hipEvent_t passed as void*, HOST handles owned by the caller).  A call whose batch fits one token group
+ * (at most 64 tokens and 16 / 16 / 10 / 8 experts with tokens at 1 / 2 / 3 / 4 bits) has exactly one streaming
+ * kernel between the two; a larger batch also has the helper kernels of the later groups in between.
  * One-shot; two NULLs cancel. */
 mes_status mes_time_next_call(void* start_event, void* stop_event);
 

@@ -32,7 +32,7 @@ static mes_status check_dims(int d_in, int d_out) {
 }
 
 static mes_status check_quant(int bits, int grid, int policy, bool allow_given) {
-  if (bits < 1 || bits > 3) return fail(MES_ERR_BITS, "bits must be 1, 2 or 3 (got %d)", bits);
+  if (bits < 1 || bits > 4) return fail(MES_ERR_BITS, "bits must be 1, 2, 3 or 4 (got %d)", bits);
   if (grid != MES_GRID_SYM && grid != MES_GRID_EQ1) return fail(MES_ERR_BITS, "unknown grid %d", grid);
   if (grid == MES_GRID_EQ1 && bits == 1) return fail(MES_ERR_BITS, "the Eq. 1 grid is undefined for bits = 1");
   if (policy < MES_STEP_GIVEN || policy > MES_STEP_MEANABS) return fail(MES_ERR_BITS, "unknown step policy %d", policy);
@@ -56,7 +56,7 @@ size_t mes_base_bytes(int d_in, int d_out) {
 }
 
 size_t mes_codes_bytes(int d_in, int d_out, int bits) {
-  if (d_in <= 0 || d_out <= 0 || bits < 1 || bits > 3) return 0;
+  if (d_in <= 0 || d_out <= 0 || bits < 1 || bits > 4) return 0;
   return (size_t)ceil_to(d_out, kRowPad) * ceil_to(d_in, kColPad) * bits / 8;
 }
 

@@ -121,23 +121,26 @@ __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
 // block itself provides the two wait states the hardware needs between a vector-ALU write of an operand
 // register and a matrix instruction reading it.  (Same opcode, same register as source C and destination:
 // back-to-back issue needs no further wait states.)
-__device__ __forceinline__ void mfma_fp4_fp8_pair(f32x4& acc, u32x4 a, v8i bhi, v8i blo, int scale_b) {
+// scale_a is A's block scale byte: 127 for 2^0; the high plane of 4-bit codes takes 129 (its codes count four times).
+__device__ __forceinline__ void mfma_fp4_fp8_pair(f32x4& acc, u32x4 a, v8i bhi, v8i blo, int scale_b, int scale_a = 127) {
   asm volatile("s_nop 1\n\t"
                "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4\n\t"
                "v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %3, %0, %4, %5 op_sel_hi:[0,0,0] cbsz:4"
-               : "+v"(acc) : "v"(a), "v"(bhi), "v"(blo), "v"(127), "v"(scale_b));
+               : "+v"(acc) : "v"(a), "v"(bhi), "v"(blo), "v"(scale_a), "v"(scale_b));
 }
 
-// Code words of one slot for one (chunk, row tile): LW low words per lane and, for b = 3, one word of high bits.
+// Code words of one slot for one (chunk, row tile): LW low words per lane and HW words of high bits (b = 3: one
+// word, the third bit; b = 4: two words, the high two bits laid out like the low two).
 template <int BITS> struct Codec;
-template <> struct Codec<2> { static constexpr int LW = 2; };
-template <> struct Codec<1> { static constexpr int LW = 1; };
-template <> struct Codec<3> { static constexpr int LW = 2; };
+template <> struct Codec<2> { static constexpr int LW = 2, HW = 0; };
+template <> struct Codec<1> { static constexpr int LW = 1, HW = 0; };
+template <> struct Codec<3> { static constexpr int LW = 2, HW = 1; };
+template <> struct Codec<4> { static constexpr int LW = 2, HW = 2; };
 
 template <int BITS>
 struct CodeRegs {
   uint32_t lo[Codec<BITS>::LW];
-  uint32_t hi;
+  uint32_t hi[Codec<BITS>::HW > 0 ? Codec<BITS>::HW : 1];
 };
 
 // Bytes of one (chunk, row tile) block of a slot's codes.
@@ -152,7 +155,11 @@ __device__ __forceinline__ void load_codes(const char* blk, int lane, CodeRegs<B
   } else {
     const u32x2 v = *reinterpret_cast<const u32x2*>(blk + (uint32_t)lane * 8u);
     r.lo[0] = v[0]; r.lo[1] = v[1];
-    if constexpr (BITS == 3) r.hi = *reinterpret_cast<const uint32_t*>(blk + 512 + (uint32_t)lane * 4u);
+    if constexpr (BITS == 3) r.hi[0] = *reinterpret_cast<const uint32_t*>(blk + 512 + (uint32_t)lane * 4u);
+    if constexpr (BITS == 4) {
+      const u32x2 h = *reinterpret_cast<const u32x2*>(blk + 512 + (uint32_t)lane * 8u);
+      r.hi[0] = h[0]; r.hi[1] = h[1];
+    }
   }
 }
 
@@ -172,10 +179,16 @@ __device__ __forceinline__ u32x4 dequant_lo(const CodeRegs<BITS>& r) {
 
 // High code bit (b = 3) as an fp4 A operand: nibble 0h00 = 2 h = (4 h) / 2.
 __device__ __forceinline__ u32x4 dequant_hi(const CodeRegs<3>& r) {
-  const uint32_t w = r.hi;
+  const uint32_t w = r.hi[0];
   u32x4 a;
   a[0] = (w << 2) & 0x44444444u; a[1] = (w << 1) & 0x44444444u; a[2] = w & 0x44444444u; a[3] = (w >> 1) & 0x44444444u;
   return a;
+}
+
+// High two code bits (b = 4) as an fp4 A operand: values h / 2; the matrix instruction scales them by four.
+__device__ __forceinline__ u32x4 dequant_hi(const CodeRegs<4>& r) {
+  const uint32_t w0 = r.hi[0], w1 = r.hi[1];
+  return u32x4{w0 & 0x33333333u, (w0 >> 2) & 0x33333333u, w1 & 0x33333333u, (w1 >> 2) & 0x33333333u};
 }
 
 // fp32 -> bf16 bits, round to nearest even.
@@ -563,7 +576,8 @@ struct Stream {
         *reinterpret_cast<uint32_t*>(dst + lane * 4) = r.lo[0];
       } else {
         *reinterpret_cast<u32x2*>(dst + lane * 8) = u32x2{r.lo[0], r.lo[1]};
-        if constexpr (BITS == 3) *reinterpret_cast<uint32_t*>(dst + 512 + lane * 4) = r.hi;
+        if constexpr (BITS == 3) *reinterpret_cast<uint32_t*>(dst + 512 + lane * 4) = r.hi[0];
+        if constexpr (BITS == 4) *reinterpret_cast<u32x2*>(dst + 512 + lane * 8) = u32x2{r.hi[0], r.hi[1]};
       }
     }
   }
@@ -590,7 +604,7 @@ struct Stream {
   }
 
   // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
-  static constexpr int kYounger = NA * (BITS == 3 ? 2 : 1) + 4 + TT + 2 * kSalPerChunk;
+  static constexpr int kYounger = NA * (BITS >= 3 ? 2 : 1) + 4 + TT + 2 * kSalPerChunk;
 
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
   template <int BUF>
@@ -626,10 +640,10 @@ struct Stream {
         const int sc = slot_tok[tt] == (uint32_t)a ? scale[BUF][tt] : 0;
         const u32x4 d = dequant_lo<BITS>(cr);
         u32x4 h;
-        if constexpr (BITS == 3) h = dequant_hi(cr);
+        if constexpr (BITS >= 3) h = dequant_hi(cr);
         cr = parked(a < last ? a + 1 : a);   // the next visit's words, fetched while this one multiplies
         mfma_fp4_fp8_pair(acc_raw[tt], d, bhi, blo, sc);
-        if constexpr (BITS == 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc);
+        if constexpr (BITS >= 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc, BITS == 4 ? 129 : 127);
       } while (++a <= last);
       if (tt + 1 < TT) { bhi = lds_fp8(cur, pt(tt + 1), 0, lane); blo = lds_fp8(cur, pt(tt + 1), 1, lane); }
 #pragma unroll
@@ -813,7 +827,7 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p)
 
 // Active experts one launch handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
 // 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
-constexpr int max_pass_slots(int bits) { return bits == 3 ? 10 : 16; }
+constexpr int max_pass_slots(int bits) { return bits == 4 ? 8 : bits == 3 ? 10 : 16; }
 
 // Wavefronts per workgroup (each owns 16 output channels): 8 fill a compute unit's four SIMDs two deep; 7 or 6
 // are chosen when that makes the number of workgroups fit the 256 compute units better.
@@ -1026,14 +1040,15 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     k_prepare<<<4 * p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (c.ev_start && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
+    if (c.ev_start && t0 == 0 && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
     switch (d0.bits) {
       case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
       case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
+      case 4: e = launch_na<4>(p, tt, pl.nw, grid, s); break;
       default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
     }
     if (e != hipSuccess) return e;
-    if (c.ev_stop && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;
+    if (c.ev_stop && t0 + nt >= c.T && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;
     if (pl.nsplit > 1) {
       if ((e = launch_reduce(p, tt, pl.nw, grid.x, s)) != hipSuccess) return e;
     }

@@ -127,7 +127,7 @@ __global__ void k_row_step(const float* __restrict__ delta, int d_in, const int3
 struct CodeLoc {
   size_t lo_word;   // index of the 32-bit word holding the low bits (all bits for b = 1, 2)
   int lo_shift;
-  size_t hi_word;   // b = 3: word holding the high bit
+  size_t hi_word;   // b = 3: word holding the high bit; b = 4: word holding the high two bits
   int hi_shift;
 };
 
@@ -144,8 +144,13 @@ __device__ __forceinline__ CodeLoc code_location(int bits, int n_jt, int row, in
   } else {
     L.lo_word = blk + lane * 2 + (q >> 1);
     L.lo_shift = 4 * pp + 2 * (q & 1);
-    L.hi_word = blk + 128 + lane;
-    L.hi_shift = 4 * pp + q;
+    if (bits == 4) {   // a second 2-bit block
+      L.hi_word = blk + 128 + lane * 2 + (q >> 1);
+      L.hi_shift = 4 * pp + 2 * (q & 1);
+    } else {
+      L.hi_word = blk + 128 + lane;
+      L.hi_shift = 4 * pp + q;
+    }
   }
   return L;
 }
@@ -168,11 +173,11 @@ __global__ void k_pack_codes(const float* __restrict__ delta, int d_in, int d_ou
     if (is_salient(sidx, k, col, nullptr)) continue;
     const uint32_t u = quant_code(r[col], s, bits, grid);
     const CodeLoc L = code_location(bits, n_jt, row, col);
-    lo_bits |= (bits == 3 ? (u & 3u) : u) << L.lo_shift;
-    if (bits == 3) hi_bits |= (u >> 2) << L.hi_shift;
+    lo_bits |= (bits >= 3 ? (u & 3u) : u) << L.lo_shift;
+    if (bits >= 3) hi_bits |= (u >> 2) << L.hi_shift;
   }
   if (lo_bits) atomicOr(out + L0.lo_word, lo_bits);
-  if (bits == 3 && hi_bits) atomicOr(out + L0.hi_word, hi_bits);
+  if (bits >= 3 && hi_bits) atomicOr(out + L0.hi_word, hi_bits);
 }
 
 // `flag` was written by k_check_salient earlier on the same stream: with indices that failed the check
@@ -204,7 +209,7 @@ __device__ __forceinline__ uint32_t load_code(const uint32_t* codes, int bits, i
   if (bits == 1) return (codes[L.lo_word] >> L.lo_shift) & 1u;
   const uint32_t lo = (codes[L.lo_word] >> L.lo_shift) & 3u;
   if (bits == 2) return lo;
-  return lo | (((codes[L.hi_word] >> L.hi_shift) & 1u) << 2);
+  return lo | (((codes[L.hi_word] >> L.hi_shift) & (bits == 4 ? 3u : 1u)) << 2);
 }
 
 __global__ void k_unpack_delta(const uint32_t* __restrict__ codes, const float* __restrict__ step,

@@ -57,7 +57,7 @@ def test_pack_base_matches_oracle_layout(d_out, d_in):
     assert torch.equal(back.cpu().view(torch.int16), w.view(torch.int16))
 
 
-@pytest.mark.parametrize("bits,grid,policy", [(2, 0, 1), (1, 0, 1), (3, 0, 1), (2, 1, 1), (3, 1, 1), (1, 0, 2)])
+@pytest.mark.parametrize("bits,grid,policy", [(2, 0, 1), (1, 0, 1), (3, 0, 1), (4, 0, 1), (2, 1, 1), (3, 1, 1), (4, 1, 1), (1, 0, 2)])
 @pytest.mark.parametrize("d_out,d_in,k", [(256, 256, 8), (72, 264, 5), (64, 1032, 33), (132, 520, 0)])
 def test_pack_delta_bit_exact(bits, grid, policy, d_out, d_in, k):
     ex = synth.make_delta(d_in, d_out, k, 0.003, 15.0, 5000 + bits * 7 + d_in)
@@ -97,7 +97,7 @@ def test_pack_delta_rejects_bad_salient_indices():
         assert e.value.status == 4
 
 
-@pytest.mark.parametrize("bits,grid", [(2, 0), (2, 1), (3, 0), (1, 0)])
+@pytest.mark.parametrize("bits,grid", [(2, 0), (2, 1), (3, 0), (1, 0), (4, 1)])
 def test_select_salient_indices_bit_exact(bits, grid):
     d_out, d_in, n, k = 96, 264, 40, 8
     ex = synth.make_delta(d_in, d_out, k, 0.003, 15.0, 900 + bits)
@@ -131,7 +131,7 @@ def test_config1():
     assert rel_fro(y, y_ref) <= TOL
 
 
-@pytest.mark.parametrize("bits,grid,policy", [(2, 0, 1), (1, 0, 1), (1, 0, 2), (3, 0, 1), (2, 1, 1), (3, 1, 1)])
+@pytest.mark.parametrize("bits,grid,policy", [(2, 0, 1), (1, 0, 1), (1, 0, 2), (3, 0, 1), (2, 1, 1), (3, 1, 1), (4, 0, 1), (4, 1, 1)])
 def test_config1_all_bit_widths_and_grids(bits, grid, policy):
     wl = synth.config1()
     wl.bits = bits
@@ -146,6 +146,7 @@ def test_config1_all_bit_widths_and_grids(bits, grid, policy):
     (2048, 320, [0, 0, 0, 5], 16, 2),            # leading empty experts
     (512, 64, [0, 16, 32, 48, 64], 32, 2),       # tile-aligned segments
     (4096, 192, [0, 7, 30, 31, 50, 61], 64, 2),  # several column splits, ragged token tail
+    (1160, 200, [0, 5, 5, 21, 40, 64], 24, 4),   # 4-bit codes, ragged shape
 ])
 def test_ragged_shapes_and_segments(d_in, d_out, seg, k, bits):
     wl = synth.small_case(d_in, d_out, seg, k, bits, seed=d_in % 97)
@@ -271,10 +272,10 @@ def test_config4_sampled_rows_at_full_size():
     assert sum(1 for e in range(16) if wl.seg_offsets[e + 1] > wl.seg_offsets[e]) >= 8
 
 
-@pytest.mark.parametrize("bits", [1, 2, 3])
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
 def test_more_experts_than_one_pass_holds(bits):
     """40 experts, most with one or two tokens, in one 64-token batch: the token group has to be cut where the
-    kernel's expert slots run out (16, or 10 at 3 bits), with empty experts sprinkled in."""
+    kernel's expert slots run out (16, 10 at 3 bits, 8 at 4 bits), with empty experts sprinkled in."""
     seg = [0]
     for e in range(40):
         seg.append(seg[-1] + (1, 2, 0, 1, 3, 1, 2, 1)[e % 8])      # 55 tokens, 35 experts with tokens
@@ -294,7 +295,7 @@ def sampled_rows_check(wl, y, n_rows, seed):
     return rel_fro(y[:, rows], y_ref)
 
 
-@pytest.mark.parametrize("bits,which", [(1, "down_proj"), (3, "down_proj"), (3, "q_proj")])
+@pytest.mark.parametrize("bits,which", [(1, "down_proj"), (3, "down_proj"), (3, "q_proj"), (4, "down_proj"), (4, "q_proj")])
 def test_config4_other_bit_widths_at_full_size(bits, which):
     """The 1- and 3-bit code paths at a full Mistral-7B shape with 16 experts (the 14336-wide input of
     down_proj is the longest reduction any config has)."""

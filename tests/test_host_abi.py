@@ -30,11 +30,11 @@ def test_size_functions_match_the_layout_specification():
     for d_in, d_out, k in [(256, 256, 8), (4096, 4096, 64), (14336, 4096, 128), (4096, 14336, 64), (264, 72, 5), (8, 4, 0)]:
         po, pi, pk = O.padded_dims(d_out, d_in, k)
         assert lib.mes_base_bytes(d_in, d_out) == po * pi * 2
-        for bits in (1, 2, 3):
+        for bits in (1, 2, 3, 4):
             assert lib.mes_codes_bytes(d_in, d_out, bits) == O.codes_bytes(d_in, d_out, bits)
         assert lib.mes_salient_bytes(d_out, k) == po * pk * 2
         assert lib.mes_linear_workspace_bytes(d_in, d_out, 64) >= po // 16 * 4
-    assert lib.mes_codes_bytes(4096, 4096, 4) == 0
+    assert lib.mes_codes_bytes(4096, 4096, 5) == 0
     assert lib.mes_base_bytes(0, 4) == 0
 
 
@@ -57,7 +57,7 @@ def test_pack_delta_argument_errors():
              step=FAKE, sal=FAKE, ws=FAKE, wsb=256):
         return lib.mes_pack_delta(delta, d_in, d_out, sidx, k, bits, grid, pol, step_in, codes, step, sal, ws, wsb, None)
     assert call(delta=None) == 1
-    assert call(bits=0) == 3 and call(bits=4) == 3
+    assert call(bits=0) == 3 and call(bits=5) == 3
     assert call(bits=1, grid=1) == 3                               # Eq. 1 grid has no 1-bit form
     assert call(grid=2) == 3
     assert call(pol=2, bits=2) == 3                                # MEANABS is the binary scale
