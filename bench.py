@@ -82,7 +82,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="c4", choices=["c4", "c2"])
     ap.add_argument("--bits", type=int, default=2)
+    ap.add_argument("--k", type=int, default=64, help="salient fp16 input channels per expert (c4 only)")
+    ap.add_argument("--grid", default="sym", choices=["sym", "eq1"], help="quantisation grid (eq1 needs bits >= 2)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-frac", type=int, default=0, help="oracle leg: 1/N of the output channels (default 2 for c4)")
     ap.add_argument("--breakdown", action="store_true", help="also time every call on its own (stderr)")
     ap.add_argument("--unfused", action="store_true", help="seven single-layer calls per step instead of four")
     ap.add_argument("--copy-probe", action="store_true",
@@ -114,7 +117,7 @@ def main():
     g = torch.Generator().manual_seed(4242)
     if args.workload == "c4":
         names = [n for n, _, _ in synth.MISTRAL7B_LINEARS]
-        wls = [(n, lambda n=n: synth.config4_linear(n, device=dev, bits=args.bits)) for n in names]
+        wls = [(n, lambda n=n: synth.config4_linear(n, device=dev, bits=args.bits, k=args.k)) for n in names]
         sample_frac = 2
         copies = 1
     else:
@@ -127,7 +130,8 @@ def main():
         wl = make()
         T = wl.x.shape[0]
         w_t = mes.mes_pack_base(wl.w_base)
-        packed = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]
+        grid = mes.GRID_EQ1 if args.grid == "eq1" else mes.GRID_SYM
+        packed = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits, grid) for ex in wl.experts]
         lin = mes.DeltaLinear(w_t, packed, T)
         y = torch.empty((T, wl.d_out), dtype=torch.bfloat16, device=dev)
         n_active = sum(1 for e in range(len(packed)) if wl.seg_offsets[e + 1] > wl.seg_offsets[e])
@@ -135,7 +139,7 @@ def main():
                            k=wl.k, bits=wl.bits, n_active=n_active,
                            bytes=algorithmic_bytes(wl.d_in, wl.d_out, wl.k, wl.bits, n_active, T)))
         if not args.no_cpu_baseline and (args.workload == "c4" or len(samples) == 0):
-            rows = torch.sort(torch.randperm(wl.d_out, generator=g)[: max(wl.d_out // sample_frac, 16)]).values
+            rows = torch.sort(torch.randperm(wl.d_out, generator=g)[: max(wl.d_out // (args.sample_frac or sample_frac), 16)]).values
             rd = rows.to(dev)
             samples.append(dict(name=name, rows=rows, layer=len(layers) - 1,
                                 w=wl.w_base[rd].double().cpu().numpy(), x=wl.x.double().cpu().numpy(),
@@ -243,8 +247,9 @@ def main():
         for s in samples:           # offline compression of the sampled rows is not part of the timed oracle work
             exs = []
             for d, si in zip(s["deltas"], s["sidx"]):
-                c, st, sal = O.quantize(d, si, s["bits"])
-                exs.append(dict(codes=c, step=st, salient=sal, salient_idx=si, bits=s["bits"], grid=O.GRID_SYM))
+                og = O.GRID_EQ1 if args.grid == "eq1" else O.GRID_SYM
+                c, st, sal = O.quantize(d, si, s["bits"], og)
+                exs.append(dict(codes=c, step=st, salient=sal, salient_idx=si, bits=s["bits"], grid=og))
             prepared.append(exs)
         t0 = time.perf_counter()
         refs = [O.delta_linear(s["x"], s["w"], exs, s["seg"]) for s, exs in zip(samples, prepared)]
@@ -277,7 +282,7 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": ("c4: 7 Mistral-7B linear shapes of one block, 16 experts, 64 decode tokens, Zipf(1.1) routing, "
-                                f"{args.bits}-bit codes, 64 fp16 salient channels") if args.workload == "c4" else
+                                f"{args.bits}-bit codes ({args.grid} grid), {args.k} fp16 salient channels") if args.workload == "c4" else
                                "c2: Mistral-7B q_proj 4096x4096, 3 experts, 48 decode tokens 16/16/16, 2-bit, 64 salient; "
                                f"{copies} rotating copies",
                    "tokens": T, "experts": 16 if args.workload == "c4" else 3, "bits": args.bits,

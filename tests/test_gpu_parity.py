@@ -335,3 +335,19 @@ def test_config3_prefill_sampled_rows(bits, which):
     torch.cuda.synchronize()
     assert y.shape == (1536, wl.d_out)
     assert sampled_rows_check(wl, y, 64, 11 + bits) <= TOL
+
+
+@pytest.mark.parametrize("k,bits,grid", [(8, 2, 1), (32, 2, 0), (16, 4, 1), (0, 2, 0)])
+def test_config4_salient_counts_and_eq1_grid_at_full_size(k, bits, grid):
+    """The paper's sweep of the number of fp16 channels (8 to 64) and the Eq. 1 grid, at the o_proj shape with 16
+    experts; k = 0 is the fixed-precision baseline of the paper's comparison."""
+    wl = synth.config4_linear("o_proj", device=DEV, bits=bits, k=k)
+    w_t = mes.mes_pack_base(wl.w_base)
+    ge = [mes.mes_pack_delta(ex.delta, ex.salient_idx if k else None, wl.bits, grid) for ex in wl.experts]
+    y = mes.mes_delta_linear(w_t, ge, wl.x, wl.seg_offsets)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(17 + k)
+    rows = torch.sort(torch.randperm(wl.d_out, generator=g)[:96]).values.to(DEV)
+    oe = oracle_experts(wl, grid=grid, rows=rows)
+    y_ref = O.delta_linear(wl.x.double().cpu().numpy(), wl.w_base[rows].double().cpu().numpy(), oe, wl.seg_offsets)
+    assert rel_fro(y[:, rows], y_ref) <= TOL
