@@ -187,6 +187,35 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
  * One-shot; two NULLs cancel. */
 mes_status mes_time_next_call(void* start_event, void* stop_event);
 
+/* ---- on-demand swapping (Section 4.1, "On-demand swapping": the base model stays on the GPU, the compressed
+ * deltas of the experts a batch needs are loaded when they are needed) ----------------------------------------
+ * A pool serves ONE linear layer.  It owns nothing but its bookkeeping: the caller gives it a DEVICE arena of
+ * n_slots * mes_pool_slot_bytes(...) bytes (256-byte aligned; a slot holds one expert's codes, steps, salient
+ * tile and salient indices) and registers up to n_experts experts whose packed buffers (exactly the buffers
+ * mes_pack_delta writes, copied to the host) sit in PINNED HOST memory that stays valid and unchanged while
+ * registered.  Not thread-safe: one thread drives a pool.
+ *
+ * mes_pool_acquire(pool, experts[n], ...): makes the n distinct experts resident and writes their descriptors
+ * to out[n] (HOST array), in the order asked.  An expert already in a slot is a hit.  A miss overwrites the
+ * least recently acquired slot that holds none of this request's experts (never-used slots first, lowest slot
+ * index among equals) with asynchronous host-to-device copies on `copy_stream`; these copies start only
+ * after everything enqueued on `compute_stream` so far (a kernel may still read the slot), and
+ * `compute_stream` is made to wait for them, so work enqueued on it after the call sees the new contents.
+ * Descriptors of EARLIER acquires are stale once a later acquire has missed.  n > n_slots is MES_ERR_SHAPE.
+ * A pool created with dry_run != 0 does the bookkeeping only (no GPU call): for tests of the policy.
+ * mes_pool_stats: hits, misses and bytes copied since creation (any pointer may be NULL). */
+typedef struct mes_pool mes_pool;
+size_t mes_pool_slot_bytes(int d_in, int d_out, int k, int bits);
+mes_status mes_pool_create(int d_in, int d_out, int k, int bits, int grid, int n_slots, int n_experts, void* arena,
+                           size_t arena_bytes, int dry_run, mes_pool** out);
+void mes_pool_destroy(mes_pool* pool);
+mes_status mes_pool_register(mes_pool* pool, int expert, const void* codes, const float* step, const void* salient,
+                             const int32_t* salient_idx);
+mes_status mes_pool_acquire(mes_pool* pool, const int32_t* experts, int n, mes_delta* out, void* copy_stream,
+                            void* compute_stream);
+int mes_pool_slot_of(const mes_pool* pool, int expert);   /* slot the expert is resident in, or -1 */
+mes_status mes_pool_stats(const mes_pool* pool, uint64_t* hits, uint64_t* misses, uint64_t* bytes_copied);
+
 /* Measurement hook: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers DEVICE,
  * 16-byte aligned, not overlapping) done by one kernel, k_copy_probe.  It reads and writes exactly `bytes`
  * of HBM, which is what a profiler's memory-traffic counters are scaled by before they are compared with the

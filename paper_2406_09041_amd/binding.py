@@ -28,7 +28,8 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_select_workspace_bytes", "mes_linear_workspace_bytes", "mes_last_error", "mes_layout_version",
            "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
            "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
-           "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe"]
+           "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
+           "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats"]
 
 
 class MesError(RuntimeError):
@@ -93,6 +94,20 @@ def _load() -> ctypes.CDLL:
     lib.mes_time_next_call.argtypes = [vp, vp]
     lib.mes_copy_probe.restype = c_int
     lib.mes_copy_probe.argtypes = [vp, vp, c_sz, vp]
+    lib.mes_pool_slot_bytes.restype = c_sz
+    lib.mes_pool_slot_bytes.argtypes = [c_int, c_int, c_int, c_int]
+    lib.mes_pool_create.restype = c_int
+    lib.mes_pool_create.argtypes = [c_int, c_int, c_int, c_int, c_int, c_int, c_int, vp, c_sz, c_int, ctypes.POINTER(vp)]
+    lib.mes_pool_destroy.restype = None
+    lib.mes_pool_destroy.argtypes = [vp]
+    lib.mes_pool_register.restype = c_int
+    lib.mes_pool_register.argtypes = [vp, c_int, vp, vp, vp, vp]
+    lib.mes_pool_acquire.restype = c_int
+    lib.mes_pool_acquire.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), c_int, ctypes.POINTER(mes_delta), vp, vp]
+    lib.mes_pool_slot_of.restype = c_int
+    lib.mes_pool_slot_of.argtypes = [vp, c_int]
+    lib.mes_pool_stats.restype = c_int
+    lib.mes_pool_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     return lib
 
 
@@ -237,6 +252,18 @@ def mes_delta_linear(w_base_tiled, experts, x, seg_offsets, y=None, workspace=No
     return DeltaLinear(w_base_tiled, experts, x.shape[0], workspace)(x, seg_offsets, y)
 
 
+def mes_delta_linear_descriptors(w_base_tiled: torch.Tensor, desc, x: torch.Tensor, seg_offsets: Sequence[int],
+                                 workspace: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """mes_delta_linear on a ready ctypes array of mes_delta (e.g. what ExpertPool.acquire returns)."""
+    E, T, d_out = len(desc), x.shape[0], desc[0].d_out
+    if y is None:
+        y = torch.empty((T, d_out), dtype=torch.bfloat16, device=x.device)
+    seg = (ctypes.c_int32 * (E + 1))(*seg_offsets)
+    _check(lib.mes_delta_linear(_ptr(w_base_tiled), desc, E, _ptr(x), T, seg, _ptr(y), _ptr(workspace),
+                                workspace.numel(), _stream(x.device)))
+    return y
+
+
 class DeltaLinearMulti:
     """Marshalled arguments of mes_delta_linear_multi: several layers that read the same activations and routing."""
 
@@ -265,6 +292,71 @@ class DeltaLinearMulti:
         _check(lib.mes_delta_linear_multi(lin, self.n, self.E, _ptr(x), T, seg, _ptr(self.ws), self.ws.numel(),
                                           _stream(x.device)))
         return list(ys)
+
+
+class ExpertPool:
+    """On-demand swapping for one linear layer (mes_pool_* in mes.h): a device arena of `n_slots` slots and
+    pinned host copies of every registered expert's packed buffers."""
+
+    def __init__(self, d_in: int, d_out: int, k: int, bits: int, grid: int, n_slots: int, n_experts: int,
+                 device="cuda:0", dry_run: bool = False):
+        self.d_in, self.d_out, self.k, self.bits, self.grid = d_in, d_out, k, bits, grid
+        self.n_slots = n_slots
+        self.slot_bytes = lib.mes_pool_slot_bytes(d_in, d_out, k, bits)
+        if dry_run:
+            self.arena, arena_ptr = None, 256          # any aligned non-null address: a dry-run pool never touches it
+        else:
+            self.arena = torch.empty(self.slot_bytes * n_slots, dtype=torch.uint8, device=device)
+            arena_ptr = self.arena.data_ptr()
+            self.copy_stream = torch.cuda.Stream(device=device)
+        self.device = device
+        self.dry_run = dry_run
+        self.host = {}                                  # expert -> pinned host tensors (kept alive here)
+        h = ctypes.c_void_p()
+        _check(lib.mes_pool_create(d_in, d_out, k, bits, grid, n_slots, n_experts, arena_ptr,
+                                   self.slot_bytes * n_slots, int(dry_run), ctypes.byref(h)))
+        self.handle = h
+
+    def register(self, expert: int, packed: "PackedDelta") -> None:
+        """Copies the packed buffers to pinned host memory and registers them."""
+        def pin(t):
+            if t is None:
+                return None
+            out = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+            out.copy_(t)
+            return out
+        bufs = (pin(packed.codes), pin(packed.step), pin(packed.salient), pin(packed.salient_idx))
+        self.host[expert] = bufs
+        _check(lib.mes_pool_register(self.handle, expert, *[None if b is None else b.data_ptr() for b in bufs]))
+
+    def register_raw(self, expert: int, codes: int, step: int, salient: int, sidx: int) -> None:
+        _check(lib.mes_pool_register(self.handle, expert, codes, step, salient, sidx))
+
+    def acquire(self, experts: Sequence[int]):
+        """Makes `experts` resident; returns the ctypes array of their descriptors (valid until the next miss)."""
+        n = len(experts)
+        ids = (ctypes.c_int32 * n)(*experts)
+        out = (mes_delta * n)()
+        if self.dry_run:
+            cs = ks = None
+        else:
+            cs = self.copy_stream.cuda_stream
+            ks = _stream(torch.device(self.device))
+        _check(lib.mes_pool_acquire(self.handle, ids, n, out, cs, ks))
+        return out
+
+    def slot_of(self, expert: int) -> int:
+        return lib.mes_pool_slot_of(self.handle, expert)
+
+    def stats(self):
+        h, m, b = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib.mes_pool_stats(self.handle, ctypes.byref(h), ctypes.byref(m), ctypes.byref(b)))
+        return h.value, m.value, b.value
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            lib.mes_pool_destroy(self.handle)
+            self.handle = None
 
 
 class KernelTimer:

@@ -351,3 +351,39 @@ def test_config4_salient_counts_and_eq1_grid_at_full_size(k, bits, grid):
     oe = oracle_experts(wl, grid=grid, rows=rows)
     y_ref = O.delta_linear(wl.x.double().cpu().numpy(), wl.w_base[rows].double().cpu().numpy(), oe, wl.seg_offsets)
     assert rel_fro(y[:, rows], y_ref) <= TOL
+
+
+def test_on_demand_swapping_gives_the_resident_result():
+    """20 experts registered in pinned host memory, 6 device slots.  Every batch acquires the experts it routes to
+    (least recently used slots are overwritten) and must give, bit for bit, what the same call gives on the
+    always-resident packed deltas; one batch is also checked against the oracle, and the hit / miss counts
+    against the policy oracle."""
+    from oracle.pool_oracle import LruPool
+    d_in, d_out, k, bits, n_experts, n_slots = 520, 136, 16, 2, 20, 6
+    wl = synth.small_case(d_in, d_out, [0] + [3 * (e + 1) for e in range(n_experts)], k, bits, seed=61)   # only the experts are used
+    w_t = mes.mes_pack_base(wl.w_base.to(DEV))
+    ge = gpu_experts(wl)
+    pool = mes.ExpertPool(d_in, d_out, k, bits, 0, n_slots, n_experts, device=DEV)
+    for e, pk in enumerate(ge):
+        pool.register(e, pk)
+    ws = mes.make_workspace(d_in, d_out, 64, torch.device(DEV))
+    ref = LruPool(n_slots)
+    rng = np.random.default_rng(5)
+    oe = oracle_experts(wl)
+    for step in range(12):
+        ids = sorted(rng.choice(n_experts, size=int(rng.integers(1, n_slots + 1)), replace=False).tolist())
+        counts = rng.integers(1, 9, size=len(ids))
+        seg = [0] + np.cumsum(counts).tolist()
+        x = synth.normal((seg[-1], d_in), 1.0, 700 + step, DEV, torch.bfloat16)
+        ref.acquire(ids)
+        desc = pool.acquire(ids)
+        y_pool = mes.mes_delta_linear_descriptors(w_t, desc, x, seg, ws)
+        y_res = mes.mes_delta_linear(w_t, [ge[e] for e in ids], x, seg)
+        torch.cuda.synchronize()
+        assert torch.equal(y_pool.view(torch.int16), y_res.view(torch.int16)), f"batch {step}"
+        if step == 7:
+            y_ref = O.delta_linear(x.double().cpu().numpy(), wl.w_base.double().numpy(), [oe[e] for e in ids], seg)
+            assert rel_fro(y_pool, y_ref) <= TOL
+    hits, misses, nbytes = pool.stats()
+    assert (hits, misses) == (ref.hits, ref.misses) and misses > n_slots          # slots were really recycled
+    assert nbytes == misses * (mes.codes_bytes(d_in, d_out, bits) + 4 * d_out + mes.salient_bytes(d_out, k) + 4 * k)
