@@ -182,7 +182,7 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
  * kernel): the NEXT mes_delta_linear / mes_delta_linear_multi call of the calling thread records `start_event`
  * on its stream immediately before its first streaming kernel and `stop_event` immediately after its last one
  * (hipEvent_t passed as void*, HOST handles owned by the caller).  A call whose batch fits one token group
- * (at most 64 tokens and 16 / 16 / 10 / 8 experts with tokens at 1 / 2 / 3 / 4 bits) has exactly one streaming
+ * (at most 64 tokens routed to at most 16 experts) has exactly one streaming
  * kernel between the two; a larger batch also has the helper kernels of the later groups in between.
  * One-shot; two NULLs cancel. */
 mes_status mes_time_next_call(void* start_event, void* stop_event);

@@ -466,6 +466,11 @@ struct Stream {
   int rev;
   __device__ __forceinline__ int pt(int tt) const { return rev ? TT - 1 - tt : tt; }
   char* parkp;                // this wavefront's LDS area: [NA][kSlotLds]
+  // A launch holds up to kMaxSlots experts but only NA of them fit the registers and the LDS area at a time:
+  // the chunks are swept once per group of NA slots (`pass`), the first sweep also doing the base product.
+  // a0 = first slot of the current sweep.
+  int a0 = 0;
+  __device__ __forceinline__ const char* codes_of(int a) const { const int s = a0 + a; return L.codes[s < kMaxSlots ? s : kMaxSlots - 1]; }
   uint32_t slot_tok[TT];
   int scale[2][TT];           // per-token block scales of the current / next chunk
   u32x4 base[2][4];
@@ -562,7 +567,7 @@ struct Stream {
   __device__ __forceinline__ void load_code_regs(int c) {
     const size_t off = ((size_t)c * L.n_jt + jt) * kSlotLds;
 #pragma unroll
-    for (int a = 0; a < NA; ++a) load_codes<BITS>(L.codes[a] + off, lane, code[BUF][a]);
+    for (int a = 0; a < NA; ++a) load_codes<BITS>(codes_of(a) + off, lane, code[BUF][a]);
   }
 
   // Register buffer BUF (the chunk that starts now) -> this wavefront's LDS area.
@@ -584,16 +589,18 @@ struct Stream {
 
   // Tile tt's share of the requests of one chunk: code words of chunk c2 (two ahead) into the register buffer
   // that was just parked, base weights and scales of chunk cn (one ahead) into the other base buffer.
-  template <int BUF>
+  template <int BUF, bool NOBASE>
   __device__ __forceinline__ void request_share(int tt, int cn, int c2) {
     const size_t off = ((size_t)c2 * L.n_jt + jt) * kSlotLds;
 #pragma unroll
     for (int a = 0; a < NA; ++a)
-      if (a * TT / NA == tt) load_codes<BITS>(L.codes[a] + off, lane, code[BUF][a]);
-    const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096;
+      if (a * TT / NA == tt) load_codes<BITS>(codes_of(a) + off, lane, code[BUF][a]);
+    if constexpr (!NOBASE) {
+      const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096;
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-      if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
+      for (int kb = 0; kb < 4; ++kb)
+        if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
+    }
     scale[BUF ^ 1][tt] = *reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale + 64 * pt(tt) + (uint32_t)n * 4u);
   }
 
@@ -604,10 +611,11 @@ struct Stream {
   }
 
   // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
-  static constexpr int kYounger = NA * (BITS >= 3 ? 2 : 1) + 4 + TT + 2 * kSalPerChunk;
+  template <bool NOBASE> static constexpr int younger() { return NA * (BITS >= 3 ? 2 : 1) + (NOBASE ? 0 : 4) + TT + 2 * kSalPerChunk; }
 
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
-  template <int BUF>
+  // NOBASE: a sweep after the first -- the base product is done, only the slots of this sweep are multiplied.
+  template <int BUF, bool NOBASE>
   __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave, bool tr = false) {
 #ifdef MES_TRACE
 #define MES_CSTAMP(i) do { if (tr) MES_STAMP(i); } while (0)
@@ -627,17 +635,24 @@ struct Stream {
       // this tile's share of the next chunks' requests: spreading them over the chunk keeps the memory
       // pipeline fed without ever asking it to take a whole chunk's loads at once (which blocks the
       // wavefront, and with it the arithmetic it could be doing, until the pipeline has room)
-      request_share<BUF>(tt, cn, c2);
-      const int first = p.tile_first[pt(tt)], last = p.tile_last[pt(tt)];
+      request_share<BUF, NOBASE>(tt, cn, c2);
+      // the tile's visits among the slots of this sweep (slot numbers relative to a0); a tile with none runs
+      // slot 0 of the sweep once with every token's scale 0, like an empty tile
+      int first = p.tile_first[pt(tt)] - a0, last = p.tile_last[pt(tt)] - a0;
+      first = first < 0 ? 0 : first;
+      last = last > NA - 1 ? NA - 1 : last;
+      if (first > last) first = last = 0;
       CodeRegs<BITS> cr = parked(first);
       u32x4 xb[4];
+      if constexpr (!NOBASE) {
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + pt(tt)) * 1024 + lane * 16);
+        for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + pt(tt)) * 1024 + lane * 16);
+      }
       // every tile of the launch has at least one visit (the host gives an empty tile slot 0, whose tokens
       // are nobody's: scale 0), so there is no branch around the loop and no second copy of the accumulator
       int a = first;
       do {
-        const int sc = slot_tok[tt] == (uint32_t)a ? scale[BUF][tt] : 0;
+        const int sc = slot_tok[tt] == (uint32_t)(a + a0) ? scale[BUF][tt] : 0;
         const u32x4 d = dequant_lo<BITS>(cr);
         u32x4 h;
         if constexpr (BITS >= 3) h = dequant_hi(cr);
@@ -646,8 +661,10 @@ struct Stream {
         if constexpr (BITS >= 3) mfma_fp4_fp8_pair(acc_raw[tt], h, bhi, blo, sc, BITS == 4 ? 129 : 127);
       } while (++a <= last);
       if (tt + 1 < TT) { bhi = lds_fp8(cur, pt(tt + 1), 0, lane); blo = lds_fp8(cur, pt(tt + 1), 1, lane); }
+      if constexpr (!NOBASE) {
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
+        for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
+      }
       if (tt == 0) sal_address();
       MES_CSTAMP(4 + tt);
     }
@@ -659,7 +676,7 @@ struct Stream {
     // different times -- the 64 KiB of LDS writes spread out and fill what would be waiting at the barrier.
     park<BUF ^ 1>();
     MES_CSTAMP(8);
-    stage_barrier<kYounger>();
+    stage_barrier<younger<NOBASE>()>();
     MES_CSTAMP(9);
   }
 };
@@ -686,12 +703,13 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | parked code words, one private area per wavefront |
   //   per wavefront and slot the 16 steps | per token (correction, salient scale)
   constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
-  constexpr int kStepBytes = NW * NA * 16 * 4;
+  constexpr int kLaunchSlots = NA == 4 ? 4 : kMaxSlots;   // experts of one launch; NA of them per sweep
+  constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
   __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + 256];
   char* const stage0 = lds;
   char* const stage1 = lds + kStageLds;
   char* const park_all = lds + 2 * kStageLds;
-  float (*step_lds)[NA][16] = reinterpret_cast<float (*)[NA][16]>(lds + 2 * kStageLds + kParkBytes);
+  float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + 2 * kStageLds + kParkBytes);
   float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
   char* const warm_lds = lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8;   // 256 bytes nobody reads
 
@@ -738,19 +756,20 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // first split applies it.)
   const int st_a = lane >> 2, st_j = 16 * jt + 4 * (lane & 3);
   f32x4 st_v = {0, 0, 0, 0};
-  if (st_a < NA && st_a < p.n_act && st_j < L.d_out) st_v = *reinterpret_cast<const f32x4*>(L.step[st_a] + st_j);
+  if (st_a < kLaunchSlots && st_a < p.n_act && st_j < L.d_out) st_v = *reinterpret_cast<const f32x4*>(L.step[st_a] + st_j);
   float2 tok_v = {0.0f, 0.0f};
   if (tid < kTokGroup) tok_v = float2{sp == 0 ? L.corr[tid] : 0.0f, L.sal_scale[tid]};
   ws.sal_begin(sp);
   MES_STAMP(13);
-  if (st_a < NA) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
+  if (st_a < kLaunchSlots) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
   if (tid < kTokGroup) tok_lds[tid] = tok_v;
 
   ws.template park<0>();
   stage_barrier<0>();
   // Salient pairs beyond what the chunks of this workgroup can carry (short column ranges with many visits)
   // are multiplied here, one at a time; then the first chunk's pairs are requested.
-  while (ws.sal_left > S::kSalPerChunk * len) {
+  const int n_sweeps = p.n_act > NA ? (p.n_act + NA - 1) / NA : 1;
+  while (ws.sal_left > S::kSalPerChunk * len * n_sweeps) {
     ws.sal_lookup();
     ws.sal_address();
     ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
@@ -761,9 +780,26 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
   MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
-    ws.template chunk<0>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
+    ws.template chunk<0, false>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
     if (i + 1 >= len) break;
-    ws.template chunk<1>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+    ws.template chunk<1, false>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+  }
+  // Further sweeps over the same chunks for the slots beyond the first NA: activations again (from L2), these
+  // slots' code words, no base weights.  The last barrier of the sweep before has every wavefront done with
+  // both stages.
+  for (int sweep = 1; sweep < n_sweeps; ++sweep) {
+    ws.a0 = sweep * NA;
+    stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
+    ws.template load_scales<0>(chunk_at(0));
+    ws.template load_code_regs<0>(chunk_at(0));
+    ws.template load_code_regs<1>(chunk_at(1));
+    ws.template park<0>();
+    stage_barrier<0>();
+    for (int i = 0; i < len; i += 2) {
+      ws.template chunk<0, true>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave);
+      if (i + 1 >= len) break;
+      ws.template chunk<1, true>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+    }
   }
 
   // epilogue: remove the zero point, apply the expert's step (the salient product is already in acc_base).
@@ -977,8 +1013,9 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   }
   p.nsplit = pl.nsplit;
   const dim3 grid(rgs, pl.nsplit);
-  // Token groups: up to 64 consecutive tokens that belong to at most max_pass_slots experts.
-  const int max_slots = max_pass_slots(d0.bits);
+  // Token groups: up to 64 consecutive tokens that belong to at most kMaxSlots experts (the kernel sweeps the
+  // chunks once per max_pass_slots of them).
+  const int max_slots = kMaxSlots;
   int e_cur = 0;   // first expert that may own token t0
   for (int t0 = 0; t0 < c.T;) {
     while (c.seg[e_cur + 1] <= t0) ++e_cur;
