@@ -202,7 +202,9 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
       return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
   }
   if (!aligned16(x)) return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
-  const size_t need = mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, T);
+  // the streaming path's share is what a call needs; the one-product scratch (sizes asked for with max_tokens >= 192)
+  // is used when it is there
+  const size_t need = mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, 1);
   if (!workspace || workspace_bytes < need) return fail(MES_ERR_WORKSPACE, "%s: workspace needs %zu bytes", who, need);
   if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "%s: workspace must be 16-byte aligned", who);
   LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, g_ev_start, g_ev_stop};

@@ -967,9 +967,19 @@ unsigned long long* g_trace = nullptr;
 int g_call = 0;
 #endif
 
+// Expert segments at least this long take the one-product path of mes_prefill.hip (materialised W + Delta~ and a
+// dense GEMM) when the workspace has room for it: from here on it is cheaper than streaming the weights once
+// per 64 tokens.
+constexpr int kPrefillMin = 192;
+
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
-  (void)max_tokens;  // one 64-token group is in flight at a time
-  return workspace_layout(d_in, d_out, n_linears).total;
+  size_t n = workspace_layout(d_in, d_out, n_linears).total;   // one 64-token group is in flight at a time
+  if (max_tokens >= kPrefillMin) {
+    int mx = 0;
+    for (int l = 0; l < n_linears; ++l) mx = d_out[l] > mx ? d_out[l] : mx;
+    n = (n + 255) / 256 * 256 + prefill_scratch_bytes(d_in, mx);
+  }
+  return n;
 }
 
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
@@ -1016,10 +1026,13 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   // Token groups: up to 64 consecutive tokens that belong to at most kMaxSlots experts (the kernel sweeps the
   // chunks once per max_pass_slots of them).
   const int max_slots = kMaxSlots;
+  bool first_kernel = true;   // measurement hook: the start event goes before the first streaming kernel / GEMM
+  // the streaming (decode) path over the tokens [t_lo, t_hi)
+  auto run_range = [&](int t_lo, int t_hi) -> hipError_t {
   int e_cur = 0;   // first expert that may own token t0
-  for (int t0 = 0; t0 < c.T;) {
+  for (int t0 = t_lo; t0 < t_hi;) {
     while (c.seg[e_cur + 1] <= t0) ++e_cur;
-    int nt = c.T - t0 < kTokGroup ? c.T - t0 : kTokGroup;
+    int nt = t_hi - t0 < kTokGroup ? t_hi - t0 : kTokGroup;
     {   // cut the group where one expert too many would start
       int act = 0;
       for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
@@ -1077,7 +1090,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     k_prepare<<<4 * p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (c.ev_start && t0 == 0 && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
+    if (c.ev_start && first_kernel && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
+    first_kernel = false;
     switch (d0.bits) {
       case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
       case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
@@ -1085,13 +1099,36 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
     }
     if (e != hipSuccess) return e;
-    if (c.ev_stop && t0 + nt >= c.T && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;
+    if (c.ev_stop && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;   // re-recorded by every later one
     if (pl.nsplit > 1) {
       if ((e = launch_reduce(p, tt, pl.nw, grid.x, s)) != hipSuccess) return e;
     }
     t0 += nt;
   }
   return hipSuccess;
+  };   // run_range
+
+  // Long expert segments go to the one-product path, everything between them to the streaming path.
+  int mx_out = 0;
+  for (int l = 0; l < c.n_linears; ++l) mx_out = d_outs[l] > mx_out ? d_outs[l] : mx_out;
+  const size_t scratch_at = (wl.total + 255) / 256 * 256;
+  const bool can_prefill = c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, mx_out) && d0.d_in <= 32767;
+  int cursor = 0;
+  for (int e = 0; can_prefill && e < c.n_experts; ++e) {
+    if (c.seg[e + 1] - c.seg[e] < kPrefillMin) continue;
+    hipError_t err = run_range(cursor, c.seg[e]);
+    if (err != hipSuccess) return err;
+    for (int l = 0; l < c.n_linears; ++l) {
+      if (c.ev_start && first_kernel && (err = hipEventRecord(c.ev_start, s)) != hipSuccess) return err;
+      first_kernel = false;
+      err = launch_prefill_segment(c.lin[l].w_base_tiled, c.lin[l].experts[e], c.x, c.seg[e], c.seg[e + 1], c.lin[l].y,
+                                   ws + scratch_at, s);
+      if (err != hipSuccess) return err;
+      if (c.ev_stop && (err = hipEventRecord(c.ev_stop, s)) != hipSuccess) return err;
+    }
+    cursor = c.seg[e + 1];
+  }
+  return run_range(cursor, c.T);
 }
 
 }  // namespace mes

@@ -387,3 +387,40 @@ def test_on_demand_swapping_gives_the_resident_result():
     hits, misses, nbytes = pool.stats()
     assert (hits, misses) == (ref.hits, ref.misses) and misses > n_slots          # slots were really recycled
     assert nbytes == misses * (mes.codes_bytes(d_in, d_out, bits) + 4 * d_out + mes.salient_bytes(d_out, k) + 4 * k)
+
+
+@pytest.mark.parametrize("d_in,d_out,seg,k,bits,grid", [
+    (520, 136, [0, 5, 305, 310, 330, 560], 16, 2, 0),     # long segments (300 and 230 tokens) between short ones
+    (1032, 72, [0, 200], 33, 3, 1),                        # one long segment only, Eq. 1 grid, 3 bits
+    (264, 200, [0, 0, 192, 400, 401], 0, 4, 0),            # exactly at the threshold, no salient channels, 4 bits
+    (512, 64, [0, 250, 260], 8, 1, 0),                     # 1 bit
+])
+def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
+    """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T from the materialised bf16 weight (a
+    dense GEMM); the rest of the batch streams as usual.  Every row against the oracle."""
+    wl = synth.small_case(d_in, d_out, seg, k, bits, seed=300 + bits)
+    y, y_ref = run_case(wl, grid)
+    assert rel_fro(y, y_ref) <= TOL
+    yg = y.double().cpu().numpy()
+    row_err = np.linalg.norm(yg - y_ref, axis=1) / np.linalg.norm(y_ref, axis=1)
+    assert row_err.max() <= 2 * TOL
+    # a workspace without the extra room keeps the whole batch on the streaming path: same result within rounding
+    w_t = mes.mes_pack_base(wl.w_base.to(DEV))
+    ge = gpu_experts(wl, grid)
+    small_ws = mes.make_workspace(d_in, d_out, 64, torch.device(DEV))
+    y_stream = mes.mes_delta_linear(w_t, ge, wl.x.to(DEV), wl.seg_offsets, workspace=small_ws)
+    torch.cuda.synchronize()
+    assert rel_fro(y_stream, y_ref) <= TOL
+    assert rel_fro(y, y_stream.double().cpu().numpy()) <= 4e-3
+
+
+def test_long_segments_in_a_fused_call():
+    d_in, seg = 512, [0, 4, 210, 230]
+    wls = [synth.small_case(d_in, d, seg, 8, 2, seed=400 + i) for i, d in enumerate([128, 72])]
+    x = wls[0].x
+    layers = [(mes.mes_pack_base(w.w_base.to(DEV)), gpu_experts(w)) for w in wls]
+    ys = mes.DeltaLinearMulti(layers, seg[-1])(x.to(DEV), seg)
+    torch.cuda.synchronize()
+    for w, y in zip(wls, ys):
+        y_ref = O.delta_linear(x.double().numpy(), w.w_base.double().numpy(), oracle_experts(w), seg)
+        assert rel_fro(y, y_ref) <= TOL
