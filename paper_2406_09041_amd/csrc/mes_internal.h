@@ -49,6 +49,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
 
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
 size_t prefill_scratch_bytes(int d_in, int max_d_out);
+bool prefill_available();
 hipError_t launch_prefill_segment(const void* w_base_tiled, const mes_delta& d, const void* x, int t_begin, int t_end,
                                   void* y, void* scratch, hipStream_t s);
 

@@ -1112,7 +1112,12 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   int mx_out = 0;
   for (int l = 0; l < c.n_linears; ++l) mx_out = d_outs[l] > mx_out ? d_outs[l] : mx_out;
   const size_t scratch_at = (wl.total + 255) / 256 * 256;
-  const bool can_prefill = c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, mx_out) && d0.d_in <= 32767;
+  bool can_prefill = c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, mx_out) && d0.d_in <= 32767;
+  if (can_prefill) {   // only ask for the GEMM library when a segment is long enough to want it
+    bool any = false;
+    for (int e = 0; e < c.n_experts; ++e) any = any || c.seg[e + 1] - c.seg[e] >= kPrefillMin;
+    can_prefill = any && prefill_available();
+  }
   int cursor = 0;
   for (int e = 0; can_prefill && e < c.n_experts; ++e) {
     if (c.seg[e + 1] - c.seg[e] < kPrefillMin) continue;

@@ -117,6 +117,12 @@ Blas* blas() {
 
 }  // namespace
 
+// False when the vendor GEMM cannot be loaded: long segments then stay on the streaming kernel.
+bool prefill_available() {
+  std::lock_guard<std::mutex> lock(g_blas_mutex);
+  return blas() != nullptr;
+}
+
 size_t prefill_scratch_bytes(int d_in, int max_d_out) {
   return (size_t)max_d_out * d_in * 2 + (((size_t)d_in * 2 + 255) / 256) * 256;
 }
