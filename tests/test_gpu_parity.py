@@ -424,3 +424,28 @@ def test_long_segments_in_a_fused_call():
     for w, y in zip(wls, ys):
         y_ref = O.delta_linear(x.double().numpy(), w.w_base.double().numpy(), oracle_experts(w), seg)
         assert rel_fro(y, y_ref) <= TOL
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_routing_and_settings(seed):
+    """Seeded random cases: shapes that are no multiple of any tile size, random routing with empty experts, every
+    bit width, both grids, any number of salient channels; batches of up to 300 tokens so that token groups, slot
+    sweeps and (sometimes) the long-segment path all occur."""
+    rng = np.random.default_rng(1000 + seed)
+    d_in = int(rng.integers(1, 160)) * 8
+    d_out = int(rng.integers(1, 70)) * 4
+    bits = int(rng.integers(1, 5))
+    grid = int(rng.integers(0, 2)) if bits > 1 else 0
+    k = int(rng.integers(0, min(d_in, 48) + 1))
+    n_experts = int(rng.integers(1, 25))
+    sizes = rng.choice([0, 0, 1, 2, 3, 5, 9, 17, 40, 70, 200], size=n_experts)
+    seg = [0] + np.cumsum(sizes).tolist()
+    if seg[-1] == 0:
+        seg[-1] = 3
+    wl = synth.small_case(d_in, d_out, seg, k, bits, seed=50 + seed)
+    y, y_ref = run_case(wl, grid)
+    assert y.shape == (seg[-1], d_out)
+    assert rel_fro(y, y_ref) <= TOL, (d_in, d_out, bits, grid, k, seg)
+    yg = y.double().cpu().numpy()
+    row_err = np.linalg.norm(yg - y_ref, axis=1) / np.maximum(np.linalg.norm(y_ref, axis=1), 1e-30)
+    assert row_err.max() <= 2.5 * TOL, (d_in, d_out, bits, grid, k, seg)
