@@ -49,14 +49,17 @@ __global__ __launch_bounds__(256) void k_materialize(const u32x4* __restrict__ b
   const int blk_id = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (blk_id >= n_blocks) return;
   const int c = blk_id / n_jt, jt = blk_id - c * n_jt;
-  const int lane = threadIdx.x & 63, g = lane >> 4, r = lane & 15, row = 16 * jt + r;
-  if (row >= d_out) return;
+  const int lane = threadIdx.x & 63, g = lane >> 4, r = lane & 15;
+  const int row = 16 * jt + r < d_out ? 16 * jt + r : d_out - 1;   // padding rows repeat the last one; never stored
+  constexpr int kTileRow = 256 + 16;
+  __shared__ __attribute__((aligned(16))) char tiles[4][16 * kTileRow];
+  char* tile = tiles[threadIdx.x >> 6];
   const uint32_t* blk = codes + (size_t)blk_id * (64 * bits);
   const float s = step[row];
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
     const int col0 = 128 * c + 32 * kb + 8 * g;
-    if (col0 >= d_in) continue;                          // padding columns of the last chunk
+    if (col0 >= d_in) continue;                          // padding columns of the last chunk: never stored
     const u32x4 b = base[((size_t)blk_id * 4 + kb) * 64 + lane];
     const int cl = 16 * kb + r, q = g;                    // the code block's lane cl owns columns 32 kb + 8 q + p
     uint32_t lo, hi = 0;
@@ -83,8 +86,16 @@ __global__ __launch_bounds__(256) void k_materialize(const u32x4* __restrict__ b
       }
       out[p] = f32_to_bf16(w + delta);
     }
-    *reinterpret_cast<u32x4*>(w_eff + (size_t)row * d_in + col0) =
+    // through the wavefront's 16 x 128 LDS tile (rows padded by 16 bytes against bank conflicts), so that the
+    // global writes below are whole 256-byte row segments
+    *reinterpret_cast<u32x4*>(tile + r * kTileRow + (32 * kb + 8 * g) * 2) =
         u32x4{out[0] | (out[1] << 16), out[2] | (out[3] << 16), out[4] | (out[5] << 16), out[6] | (out[7] << 16)};
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rr = 4 * i + (lane >> 4), cc = 128 * c + 8 * (lane & 15);   // 16 lanes cover one row's 128 columns
+    const u32x4 v = *reinterpret_cast<const u32x4*>(tile + rr * kTileRow + (lane & 15) * 16);
+    if (16 * jt + rr < d_out && cc < d_in) *reinterpret_cast<u32x4*>(w_eff + (size_t)(16 * jt + rr) * d_in + cc) = v;
   }
 }
 
