@@ -222,6 +222,35 @@ mes_status mes_pool_acquire(mes_pool* pool, const int32_t* experts, int n, mes_d
 int mes_pool_slot_of(const mes_pool* pool, int expert);   /* slot the expert is resident in, or -1 */
 mes_status mes_pool_stats(const mes_pool* pool, uint64_t* hits, uint64_t* misses, uint64_t* bytes_copied);
 
+/* ---- learning the step sizes (Section 4.1, "Efficient distillation", taken layer by layer; straight-through
+ * estimator of Section 3 for Eq. 1).  Offline. -----------------------------------------------------------------
+ * The delta weights are frozen and only the step s_j of every output channel is learned, by pulling the
+ * compressed layer towards the full-precision fine-tuned one on calibration activations x [n_tokens, d_in]
+ * (bf16).  The base product is common to both and cancels; per output channel j
+ *     r_tj = sum_i x_ti (Dtilde_ji(s_j) - delta_ji)      Dtilde of Eq. 4: b-bit columns at step s_j, fp16 salient
+ *     loss_j = 1/2 sum_t r_tj^2
+ *     grad_j = sum_t r_tj sum_{i not salient} x_ti ((u_ji - z) - [delta_ji / s_j inside the grid] delta_ji / s_j)
+ * (for bits = 1 the code does not depend on s_j: the bracket is always 0).  The codes u are decided exactly as
+ * mes_pack_delta decides them (floor / round-half-even of the exact quotient).  Arithmetic: the two operand
+ * matrices are formed in fp32 and rounded to bf16, products accumulate in fp32 on the matrix cores, the sums over
+ * tokens are fp32 in a fixed order (results are reproducible run to run).
+ * delta: fp32 [d_out, d_in], 16-byte aligned.  salient_idx: int32 [k] ascending as for mes_pack_delta (entries
+ * outside [0, d_in) are ignored), NULL if k = 0.  step: fp32 [d_out], 16-byte aligned; rows whose step is not > 0
+ * report loss 0 and grad 0.  loss_out, grad_out: fp32 [d_out], fully overwritten.  n_tokens >= 0.
+ * workspace >= mes_step_grad_workspace_bytes(d_in, d_out, n_tokens), 16-byte aligned.  Never synchronises.
+ * mes_time_next_call applies: the events bracket the one kernel that does the contractions. */
+size_t mes_step_grad_workspace_bytes(int d_in, int d_out, int n_tokens);
+mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t* salient_idx, int k, int bits, int grid,
+                         const float* step, const void* x, int n_tokens, float* loss_out, float* grad_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* One AdamW update (decoupled weight decay; the optimiser Section 5 names for this training) of n step sizes, in
+ * place, fp32: m = beta1 m + (1 - beta1) g; v = beta2 v + (1 - beta2) g^2;
+ * step = step (1 - lr weight_decay) - lr (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps).  t >= 1 is the
+ * number of this update.  step, grad, m, v: DEVICE fp32 [n]; m and v start at 0. */
+mes_status mes_step_adamw(float* step, const float* grad, float* m, float* v, int n, int t, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, void* stream);
+
 /* Measurement hook: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers DEVICE,
  * 16-byte aligned, not overlapping) done by one kernel, k_copy_probe.  It reads and writes exactly `bytes`
  * of HBM, which is what a profiler's memory-traffic counters are scaled by before they are compared with the

@@ -29,7 +29,8 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
            "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
            "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
-           "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats"]
+           "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
+           "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw"]
 
 
 class MesError(RuntimeError):
@@ -92,6 +93,13 @@ def _load() -> ctypes.CDLL:
                                            ctypes.POINTER(ctypes.c_int32), vp, c_sz, vp]
     lib.mes_time_next_call.restype = c_int
     lib.mes_time_next_call.argtypes = [vp, vp]
+    lib.mes_step_grad_workspace_bytes.restype = c_sz
+    lib.mes_step_grad_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.mes_step_grad.restype = c_int
+    lib.mes_step_grad.argtypes = [vp, c_int, c_int, vp, c_int, c_int, c_int, vp, vp, c_int, vp, vp, vp, c_sz, vp]
+    lib.mes_step_adamw.restype = c_int
+    lib.mes_step_adamw.argtypes = [vp, vp, vp, vp, c_int, c_int, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                   ctypes.c_float, ctypes.c_float, vp]
     lib.mes_copy_probe.restype = c_int
     lib.mes_copy_probe.argtypes = [vp, vp, c_sz, vp]
     lib.mes_pool_slot_bytes.restype = c_sz
@@ -216,6 +224,38 @@ def mes_select_salient(delta: torch.Tensor, x_calib: torch.Tensor, bits: int, gr
                                   step_policy, k, _ptr(idx), _ptr(score), _ptr(ws), ws.numel(), _stream(dev)))
     idx = idx[:k]
     return (idx, score) if want_scores else idx
+
+
+class StepGrad:
+    """Marshalled arguments of mes_step_grad for one delta matrix (workspace and outputs allocated once)."""
+
+    def __init__(self, delta: torch.Tensor, salient_idx: Optional[torch.Tensor], bits: int, grid: int = GRID_SYM,
+                 max_tokens: int = 512):
+        assert delta.dtype == torch.float32 and delta.is_cuda and delta.is_contiguous()
+        self.delta, self.bits, self.grid = delta, bits, grid
+        self.d_out, self.d_in = delta.shape
+        self.k = 0 if salient_idx is None else int(salient_idx.numel())
+        self.sidx = None if self.k == 0 else salient_idx.to(device=delta.device, dtype=torch.int32).contiguous()
+        self.max_tokens = max_tokens
+        n = max(lib.mes_step_grad_workspace_bytes(self.d_in, self.d_out, max_tokens), 16)
+        self.ws = torch.empty(n, dtype=torch.uint8, device=delta.device)
+        self.loss = torch.empty(self.d_out, dtype=torch.float32, device=delta.device)
+        self.grad = torch.empty(self.d_out, dtype=torch.float32, device=delta.device)
+
+    def __call__(self, step: torch.Tensor, x: torch.Tensor):
+        """step fp32 [d_out], x bf16 [n_tokens, d_in] -> (loss [d_out], grad [d_out]), overwritten by the next call."""
+        assert step.dtype == torch.float32 and x.dtype == torch.bfloat16 and x.shape[0] <= self.max_tokens
+        _check(lib.mes_step_grad(_ptr(self.delta), self.d_in, self.d_out, _ptr(self.sidx), self.k, self.bits, self.grid,
+                                 _ptr(step), _ptr(x), x.shape[0], _ptr(self.loss), _ptr(self.grad), _ptr(self.ws),
+                                 self.ws.numel(), _stream(self.delta.device)))
+        return self.loss, self.grad
+
+
+def mes_step_adamw(step: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, t: int, lr: float,
+                   beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8, weight_decay: float = 0.01) -> None:
+    """One in-place AdamW update of the step vector (and of the moments m, v)."""
+    _check(lib.mes_step_adamw(_ptr(step), _ptr(grad), _ptr(m), _ptr(v), step.numel(), t, lr, beta1, beta2, eps,
+                              weight_decay, _stream(step.device)))
 
 
 def make_workspace(d_in: int, d_out: int, max_tokens: int, device) -> torch.Tensor:

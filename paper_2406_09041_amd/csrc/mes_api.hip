@@ -226,6 +226,42 @@ mes_status mes_time_next_call(void* start_event, void* stop_event) {
   return MES_OK;
 }
 
+size_t mes_step_grad_workspace_bytes(int d_in, int d_out, int n_tokens) {
+  if (d_in <= 0 || d_out <= 0 || n_tokens < 0) return 0;
+  return step_grad_workspace_bytes(d_in, d_out, n_tokens);
+}
+
+mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t* salient_idx, int k, int bits, int grid,
+                         const float* step, const void* x, int n_tokens, float* loss_out, float* grad_out,
+                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (!delta || !step || !loss_out || !grad_out) return fail(MES_ERR_NULL, "mes_step_grad: null pointer");
+  if (mes_status st = check_dims(d_in, d_out)) return st;
+  if (mes_status st = check_quant(bits, grid, MES_STEP_GIVEN, true)) return st;
+  if (k < 0 || k > d_in) return fail(MES_ERR_SALIENT, "mes_step_grad: k = %d outside [0, %d]", k, d_in);
+  if (k > 0 && !salient_idx) return fail(MES_ERR_NULL, "mes_step_grad: k > 0 needs salient_idx");
+  if (n_tokens < 0) return fail(MES_ERR_SHAPE, "mes_step_grad: n_tokens must not be negative (got %d)", n_tokens);
+  if (n_tokens > 0 && !x) return fail(MES_ERR_NULL, "mes_step_grad: x is null");
+  if (!aligned16(delta) || !aligned16(step) || !aligned16(x))
+    return fail(MES_ERR_ALIGN, "mes_step_grad: delta, step and x must be 16-byte aligned");
+  if (!workspace || workspace_bytes < mes_step_grad_workspace_bytes(d_in, d_out, n_tokens))
+    return fail(MES_ERR_WORKSPACE, "mes_step_grad: workspace needs %zu bytes", mes_step_grad_workspace_bytes(d_in, d_out, n_tokens));
+  if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "mes_step_grad: workspace must be 16-byte aligned");
+  const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
+  g_ev_start = g_ev_stop = nullptr;
+  return check_hip(launch_step_grad(delta, d_in, d_out, salient_idx, k, bits, grid, step, x, n_tokens, loss_out, grad_out,
+                                    workspace, e0, e1, (hipStream_t)stream), "mes_step_grad");
+}
+
+mes_status mes_step_adamw(float* step, const float* grad, float* m, float* v, int n, int t, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, void* stream) {
+  if (!step || !grad || !m || !v) return fail(MES_ERR_NULL, "mes_step_adamw: null pointer");
+  if (n <= 0) return fail(MES_ERR_SHAPE, "mes_step_adamw: n must be positive (got %d)", n);
+  if (t < 1) return fail(MES_ERR_SHAPE, "mes_step_adamw: t counts updates from 1 (got %d)", t);
+  if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
+    return fail(MES_ERR_SHAPE, "mes_step_adamw: beta1 and beta2 must lie in [0, 1)");
+  return check_hip(launch_adamw(step, grad, m, v, n, t, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream), "mes_step_adamw");
+}
+
 mes_status mes_copy_probe(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src) return fail(MES_ERR_NULL, "mes_copy_probe: null buffer");
   if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return fail(MES_ERR_ALIGN, "mes_copy_probe: buffers and size must be multiples of 16 bytes");

@@ -47,6 +47,14 @@ struct LinearCall {
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens);
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
 
+// ---- implemented in mes_step.hip ---------------------------------------------------------------
+size_t step_grad_workspace_bytes(int d_in, int d_out, int n_tokens);
+hipError_t launch_step_grad(const float* delta, int d_in, int d_out, const int32_t* sidx, int k, int bits, int grid,
+                            const float* step, const void* x, int n_tokens, float* loss, float* grad, void* ws,
+                            hipEvent_t ev_start, hipEvent_t ev_stop, hipStream_t s);
+hipError_t launch_adamw(float* step, const float* grad, float* m, float* v, int n, int t, float lr, float beta1,
+                        float beta2, float eps, float weight_decay, hipStream_t s);
+
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
 size_t prefill_scratch_bytes(int d_in, int max_d_out);
 bool prefill_available();

@@ -155,6 +155,36 @@ def test_copy_probe_argument_errors():
     assert lib.mes_copy_probe(32, 24, 16, None) == 6
 
 
+def test_step_grad_argument_errors_and_workspace_size():
+    """Host-side validation of the step-learning entry points (no kernel is launched on any of these paths)."""
+    lib = B.lib
+    c_f = ctypes.c_float
+    assert lib.mes_step_grad_workspace_bytes(0, 64, 8) == 0 and lib.mes_step_grad_workspace_bytes(64, 64, -1) == 0
+    # 512 tokens, 4096 -> 14336: activations as fragments (4 MiB) + column mask + 8 token groups of partial sums
+    assert lib.mes_step_grad_workspace_bytes(4096, 14336, 512) == 4096 * 512 * 2 + 512 + 8 * 2 * 14336 * 4
+    # one token still takes a whole 256-token block of fragments
+    assert lib.mes_step_grad_workspace_bytes(128, 64, 1) == 128 * 256 * 2 + 256 + 4 * 2 * 64 * 4
+    ok = dict(delta=4096, d_in=128, d_out=64, sidx=4096, k=2, bits=2, grid=0, step=4096, x=4096, n=8, loss=4096,
+              grad=4096, ws=4096, ws_bytes=1 << 20, stream=None)
+
+    def call(**kw):
+        a = {**ok, **kw}
+        return lib.mes_step_grad(a["delta"], a["d_in"], a["d_out"], a["sidx"], a["k"], a["bits"], a["grid"], a["step"],
+                                 a["x"], a["n"], a["loss"], a["grad"], a["ws"], a["ws_bytes"], a["stream"])
+
+    assert call(delta=None) == 1 and call(loss=None) == 1 and call(x=None) == 1 and call(sidx=None) == 1
+    assert call(d_in=100) == 2 and call(n=-1) == 2
+    assert call(bits=5) == 3 and call(bits=1, grid=1) == 3
+    assert call(k=129) == 4
+    assert call(delta=4100) == 6 and call(ws=4104) == 6
+    assert call(ws=None) == 7 and call(ws_bytes=100) == 7
+    assert b"workspace" in lib.mes_last_error()
+    adam = lambda **kw: lib.mes_step_adamw(*[{**dict(s=4096, g=4096, m=4096, v=4096, n=8, t=1, lr=c_f(1e-3),
+                                                     b1=c_f(0.9), b2=c_f(0.99), eps=c_f(1e-8), wd=c_f(0.0), st=None), **kw}[k]
+                                             for k in ("s", "g", "m", "v", "n", "t", "lr", "b1", "b2", "eps", "wd", "st")])
+    assert adam(m=None) == 1 and adam(n=0) == 2 and adam(t=0) == 2 and adam(b1=c_f(1.0)) == 2
+
+
 def test_no_cpu_fallback_in_the_product_path():
     """The binding and the library sources never import or include the oracle."""
     pkg = os.path.join(ROOT, "paper_2406_09041_amd")
