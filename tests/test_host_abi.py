@@ -164,6 +164,10 @@ def test_step_grad_argument_errors_and_workspace_size():
     assert lib.mes_step_grad_workspace_bytes(4096, 14336, 512) == 4096 * 512 * 2 + 512 + 8 * 2 * 14336 * 4
     # one token still takes a whole 256-token block of fragments
     assert lib.mes_step_grad_workspace_bytes(128, 64, 1) == 128 * 256 * 2 + 256 + 4 * 2 * 64 * 4
+    # few rows: the input channels are split over workgroups (4 x 64 of them here), which leave their accumulator
+    # tiles (32 tiles of 16 bytes per thread, 512 multiplying threads) in the workspace
+    assert lib.mes_step_grad_workspace_bytes(14336, 4096, 512) == \
+        14336 * 512 * 2 + 1792 + 8 * 2 * 4096 * 4 + 4 * 64 * 32 * 512 * 16
     ok = dict(delta=4096, d_in=128, d_out=64, sidx=4096, k=2, bits=2, grid=0, step=4096, x=4096, n=8, loss=4096,
               grad=4096, ws=4096, ws_bytes=1 << 20, stream=None)
 
