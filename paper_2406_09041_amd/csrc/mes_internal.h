@@ -56,8 +56,7 @@ hipError_t launch_adamw(float* step, const float* grad, float* m, float* v, int 
                         float beta2, float eps, float weight_decay, hipStream_t s);
 
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
-size_t prefill_scratch_bytes(int d_in, int max_d_out);
-bool prefill_available();
+size_t prefill_scratch_bytes(int d_in, int max_tokens);
 hipError_t launch_prefill_segment(const void* w_base_tiled, const mes_delta& d, const void* x, int t_begin, int t_end,
                                   void* y, void* scratch, hipStream_t s);
 

@@ -967,18 +967,14 @@ unsigned long long* g_trace = nullptr;
 int g_call = 0;
 #endif
 
-// Expert segments at least this long take the one-product path of mes_prefill.hip (materialised W + Delta~ and a
-// dense GEMM) when the workspace has room for it: from here on it is cheaper than streaming the weights once
-// per 64 tokens.
+// Expert segments at least this long take the one-product path of mes_prefill.hip (W + Delta~ formed in registers,
+// one dense contraction) when the workspace has room for it: from here on it is cheaper than streaming the weights
+// once per 64 tokens.
 constexpr int kPrefillMin = 192;
 
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
   size_t n = workspace_layout(d_in, d_out, n_linears).total;   // one 64-token group is in flight at a time
-  if (max_tokens >= kPrefillMin) {
-    int mx = 0;
-    for (int l = 0; l < n_linears; ++l) mx = d_out[l] > mx ? d_out[l] : mx;
-    n = (n + 255) / 256 * 256 + prefill_scratch_bytes(d_in, mx);
-  }
+  if (max_tokens >= kPrefillMin) n = (n + 255) / 256 * 256 + prefill_scratch_bytes(d_in, max_tokens);
   return n;
 }
 
@@ -1109,15 +1105,10 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   };   // run_range
 
   // Long expert segments go to the one-product path, everything between them to the streaming path.
-  int mx_out = 0;
-  for (int l = 0; l < c.n_linears; ++l) mx_out = d_outs[l] > mx_out ? d_outs[l] : mx_out;
+  int longest = 0;
+  for (int e = 0; e < c.n_experts; ++e) longest = c.seg[e + 1] - c.seg[e] > longest ? c.seg[e + 1] - c.seg[e] : longest;
   const size_t scratch_at = (wl.total + 255) / 256 * 256;
-  bool can_prefill = c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, mx_out) && d0.d_in <= 32767;
-  if (can_prefill) {   // only ask for the GEMM library when a segment is long enough to want it
-    bool any = false;
-    for (int e = 0; e < c.n_experts; ++e) any = any || c.seg[e + 1] - c.seg[e] >= kPrefillMin;
-    can_prefill = any && prefill_available();
-  }
+  const bool can_prefill = longest >= kPrefillMin && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, longest);
   int cursor = 0;
   for (int e = 0; can_prefill && e < c.n_experts; ++e) {
     if (c.seg[e + 1] - c.seg[e] < kPrefillMin) continue;
