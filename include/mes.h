@@ -106,12 +106,12 @@ size_t mes_codes_bytes(int d_in, int d_out, int bits);   /* packed low-bit codes
 size_t mes_salient_bytes(int d_out, int k);              /* tiled fp16 salient columns          */
 size_t mes_pack_workspace_bytes(void);
 size_t mes_select_workspace_bytes(int n, int d_in, int d_out);
-/* Workspace of mes_delta_linear / _multi.  Asked for with max_tokens >= 192 it includes room for one expert's
- * effective weight W + Delta~ in bf16 (2 d_out d_in bytes): an expert segment of 192 tokens or more is then
- * computed as one dense product (Eq. 4 before decoupling: the expert's weight is written out once and
- * multiplied with the segment by the vendor bf16 GEMM, rocBLAS, loaded and initialised on first use), which
- * for long segments is several times faster than streaming the weights once per 64 tokens.  A workspace sized
- * with a smaller max_tokens is accepted by every call and keeps it on the streaming path. */
+/* Workspace of mes_delta_linear / _multi.  Asked for with max_tokens >= 192 it includes room for the long-segment
+ * path (the segment's activations re-tiled, about 4 d_in bytes per token, and up to 64 MiB of partial sums): an
+ * expert segment of 192 tokens or more is then computed as one dense product x (W + Delta~)^T (Eq. 4 before
+ * decoupling; the expert's effective weight is formed in registers, block by block, as a matrix-core operand),
+ * which for long segments is several times faster than streaming the weights once per 64 tokens.  A workspace
+ * sized with a smaller max_tokens is accepted by every call and keeps it on the streaming path. */
 size_t mes_linear_workspace_bytes(int d_in, int d_out, int max_tokens);
 size_t mes_linear_multi_workspace_bytes(int d_in, const int32_t* d_out /*HOST [n_linears]*/, int n_linears, int max_tokens);
 const char* mes_last_error(void);

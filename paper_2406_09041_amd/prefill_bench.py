@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Measures the long-segment (prefill) path on one MI355X: the three MLP shapes of a Mistral-7B block, 3 experts
 with one 512-token sequence each (1536 tokens), 128 fp16 salient channels, 2- or 3-bit codes (synthetic, seeded).
-For every matrix: time per call on the one-product path (materialised W + Delta~ and a dense bf16 GEMM) and, for
+For every matrix: time per call on the one-product path (W + Delta~ formed in registers, one fused kernel) and, for
 comparison, on the streaming path (a workspace without the extra room), tokens/s, and the fraction of the dense
 bf16 matrix-core peak reached, with 2 T d_out d_in flops per call (one product per token).  Prints one JSON object.
 """

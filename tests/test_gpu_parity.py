@@ -396,8 +396,8 @@ def test_on_demand_swapping_gives_the_resident_result():
     (512, 64, [0, 250, 260], 8, 1, 0),                     # 1 bit
 ])
 def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
-    """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T from the materialised bf16 weight (a
-    dense GEMM); the rest of the batch streams as usual.  Every row against the oracle."""
+    """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T by the fused one-product kernel (the
+    effective weight formed in registers); the rest of the batch streams as usual.  Every row against the oracle."""
     wl = synth.small_case(d_in, d_out, seg, k, bits, seed=300 + bits)
     y, y_ref = run_case(wl, grid)
     assert rel_fro(y, y_ref) <= TOL
