@@ -394,6 +394,10 @@ def test_on_demand_swapping_gives_the_resident_result():
     (1032, 72, [0, 200], 33, 3, 1),                        # one long segment only, Eq. 1 grid, 3 bits
     (264, 200, [0, 0, 192, 400, 401], 0, 4, 0),            # exactly at the threshold, no salient channels, 4 bits
     (512, 64, [0, 250, 260], 8, 1, 0),                     # 1 bit
+    (640, 136, [0, 3, 703, 710], 136, 2, 0),               # 700 tokens: 3 token blocks; 136 salient channels: 2 salient
+                                                           # steps; 136 rows: the second row group is half padding
+    (1280, 72, [0, 300, 600], 40, 3, 1),                   # two long segments, few rows: the contraction is split 3 ways
+    (2048, 520, [0, 513], 64, 4, 0),                       # 513 tokens (a ragged third token block), 4 bits
 ])
 def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
     """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T by the fused one-product kernel (the
