@@ -124,6 +124,7 @@ def test_codes_on_cell_boundaries_are_decided_exactly():
     for grid, offset in ((0, 0.0), (1, 0.5)):
         m = rng.integers(-3, 3, size=(d_out, d_in)).astype(np.float64) + offset
         delta = (m * step.astype(np.float64)[:, None]).astype(np.float32)    # the product may round: either side occurs
+        delta[:, ::7] = np.float32(-0.0)                                      # a negative zero is a zero
         ex = synth.ExpertDelta(delta=torch.from_numpy(delta), salient_idx=torch.empty(0, dtype=torch.int32))
         loss, grad = run_gpu(ex, x, step, 3, grid)
         check_case(delta, np.zeros(0, dtype=np.int64), x, step, 3, grid, loss, grad)
