@@ -85,6 +85,8 @@ def check_case(ex_delta, sidx, x, step, bits, grid, loss, grad):
     (512, 96, 257, 8, 1, 0, 1.0),         # 1 bit: sign and scale
     (1024, 260, 513, 64, 3, 1, 0.6),
     (136, 4, 9, 136, 2, 0, 1.0),          # every column salient
+    (384, 72, 1000, 6, 2, 0, 0.7),        # two 512-token blocks, the second ragged
+    (256, 64, 512, 0, 4, 0, 0.5),         # exactly one 512-token block
 ])
 def test_loss_and_gradient_against_the_oracle(d_in, d_out, n_tok, k, bits, grid, shrink):
     ex, x, step = case(d_in, d_out, n_tok, k, bits, grid, shrink, seed=bits + 4 * grid)
