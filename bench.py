@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--sample-frac", type=int, default=0, help="oracle leg: 1/N of the output channels (default 2 for c4)")
     ap.add_argument("--breakdown", action="store_true", help="also time every call on its own (stderr)")
     ap.add_argument("--unfused", action="store_true", help="seven single-layer calls per step instead of four")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step as a HIP graph and replay it in the timed region (outputs checked against eager)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the measurements run the library's plain copy kernel on 1 GiB (counter calibration)")
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"),
@@ -158,7 +160,7 @@ def main():
         Ls = [layers[i] for i in g_]
         if len(Ls) == 1:
             L = Ls[0]
-            calls.append(dict(name=L["name"], bytes=L["bytes"],
+            calls.append(dict(name=L["name"], bytes=L["bytes"], ys=[L["y"]],
                               run=(lambda L=L: L["lin"](L["x"], L["seg"], L["y"]))))
         else:
             assert all(torch.equal(L["x"], Ls[0]["x"]) and L["seg"] == Ls[0]["seg"] for L in Ls), \
@@ -167,7 +169,7 @@ def main():
             ys = [L["y"] for L in Ls]
             # the shared activations are read (and credited) once
             nbytes = sum(L["bytes"] for L in Ls) - (len(Ls) - 1) * 2 * T * Ls[0]["d_in"]
-            calls.append(dict(name="+".join(L["name"] for L in Ls), bytes=nbytes,
+            calls.append(dict(name="+".join(L["name"] for L in Ls), bytes=nbytes, ys=ys,
                               run=(lambda fused=fused, L0=Ls[0], ys=ys: fused(L0["x"], L0["seg"], ys))))
     calls_per_step = len(calls) if args.workload == "c4" else 1
 
@@ -182,11 +184,41 @@ def main():
     for i in range(args.warmup):
         one_step(i)
     torch.cuda.synchronize()
+    graph = None
+    if args.graph:
+        # One step captured as a HIP graph and replayed: same kernels, same arguments, launch overhead paid once.
+        # The library never synchronises, allocates or clears memory in these calls, so they can be captured; the
+        # replayed outputs are compared bit for bit with the eager ones below, with eager work in between.
+        assert args.workload == "c4", "--graph replays the whole c4 step"
+        eager = [[y.clone() for y in (c.get("ys") or [])] for c in calls]
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            one_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            one_step(0)
+        for _ in range(3):
+            for c in calls:
+                for y in (c.get("ys") or []):
+                    y.fill_(0)
+            graph.replay()
+            torch.cuda.synchronize()
+            for c, ref in zip(calls, eager):
+                for y, r in zip(c.get("ys") or [], ref):
+                    assert torch.equal(y, r), "graph replay differs from the eager result"
+            one_step(0)                                   # eager work between the replays
+            torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t_wall0 = time.perf_counter()
     ev0.record()
     for i in range(args.steps):
-        one_step(i)
+        if graph is not None:
+            graph.replay()
+        else:
+            one_step(i)
     ev1.record()
     torch.cuda.synchronize()
     t_wall = time.perf_counter() - t_wall0
@@ -286,7 +318,7 @@ def main():
                                "c2: Mistral-7B q_proj 4096x4096, 3 experts, 48 decode tokens 16/16/16, 2-bit, 64 salient; "
                                f"{copies} rotating copies",
                    "tokens": T, "experts": 16 if args.workload == "c4" else 3, "bits": args.bits,
-                   "calls_per_step": calls_per_step, "fused_calls": [c["name"] for c in calls] if args.workload == "c4" else None,
+                   "calls_per_step": calls_per_step, "graph_replay": bool(args.graph), "fused_calls": [c["name"] for c in calls] if args.workload == "c4" else None,
                    "active_experts": layers[0]["n_active"]},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
