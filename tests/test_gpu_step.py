@@ -94,6 +94,25 @@ def test_loss_and_gradient_against_the_oracle(d_in, d_out, n_tok, k, bits, grid,
     check_case(ex.delta.numpy(), ex.salient_idx.numpy(), x, step, bits, grid, loss, grad)
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_and_settings(seed):
+    """Seeded random cases: shapes that are no multiple of any tile size, every bit width, both grids, any number of
+    salient channels, steps from far too wide to far too narrow, a few dead rows, up to 700 tokens (one to three
+    token blocks of either kind, split input channels when the rows are few)."""
+    rng = np.random.default_rng(2000 + seed)
+    d_in = int(rng.integers(1, 150)) * 8
+    d_out = int(rng.integers(1, 80)) * 4
+    n_tok = int(rng.integers(1, 701))
+    bits = int(rng.integers(1, 5))
+    grid = int(rng.integers(0, 2)) if bits > 1 else 0
+    k = int(rng.integers(0, min(d_in - 8, 40) + 1))
+    shrink = float(rng.choice([1.5, 1.0, 0.7, 0.4, 0.2]))
+    dead = tuple(int(j) for j in rng.choice(d_out, size=min(3, d_out), replace=False)) if seed % 3 == 0 else ()
+    ex, x, step = case(d_in, d_out, n_tok, k, bits, grid, shrink, seed=30 + seed, dead_rows=dead)
+    loss, grad = run_gpu(ex, x, step, bits, grid)
+    check_case(ex.delta.numpy(), ex.salient_idx.numpy(), x, step, bits, grid, loss, grad)
+
+
 def test_dead_rows_no_tokens_and_reuse_of_a_larger_workspace():
     ex, x, step = case(264, 72, 40, 4, 2, 0, 0.8, seed=11, dead_rows=(0, 7, 71))
     sg = mes.StepGrad(ex.delta.to(DEV), ex.salient_idx, 2, 0, max_tokens=600)
