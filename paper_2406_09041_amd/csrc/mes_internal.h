@@ -57,7 +57,7 @@ hipError_t launch_adamw(float* step, const float* grad, float* m, float* v, int 
 
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
 size_t prefill_scratch_bytes(int d_in, int max_tokens);
-hipError_t launch_prefill_segment(const void* w_base_tiled, const mes_delta& d, const void* x, int t_begin, int t_end,
-                                  void* y, void* scratch, hipStream_t s);
+hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
+                                   const int32_t* seg, const void* x, void* y, void* scratch, hipStream_t s);
 
 }  // namespace mes

@@ -38,6 +38,8 @@
 // where a run-time slot number can index them.
 #include "mes_internal.h"
 
+#include <vector>
+
 #ifdef MES_TRACE
 #include <cstdio>
 #include <cstdlib>
@@ -1109,20 +1111,26 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   for (int e = 0; e < c.n_experts; ++e) longest = c.seg[e + 1] - c.seg[e] > longest ? c.seg[e + 1] - c.seg[e] : longest;
   const size_t scratch_at = (wl.total + 255) / 256 * 256;
   const bool can_prefill = longest >= kPrefillMin && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, longest);
+  // the long segments of every linear in one go (up to 8 experts per launch), then the streaming ranges between them
   int cursor = 0;
-  for (int e = 0; can_prefill && e < c.n_experts; ++e) {
-    if (c.seg[e + 1] - c.seg[e] < kPrefillMin) continue;
-    hipError_t err = run_range(cursor, c.seg[e]);
-    if (err != hipSuccess) return err;
+  if (can_prefill) {
+    std::vector<int> long_experts;
+    for (int e = 0; e < c.n_experts; ++e)
+      if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_experts.push_back(e);
     for (int l = 0; l < c.n_linears; ++l) {
+      hipError_t err;
       if (c.ev_start && first_kernel && (err = hipEventRecord(c.ev_start, s)) != hipSuccess) return err;
       first_kernel = false;
-      err = launch_prefill_segment(c.lin[l].w_base_tiled, c.lin[l].experts[e], c.x, c.seg[e], c.seg[e + 1], c.lin[l].y,
-                                   ws + scratch_at, s);
+      err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts.data(), (int)long_experts.size(),
+                                    c.seg, c.x, c.lin[l].y, ws + scratch_at, s);
       if (err != hipSuccess) return err;
       if (c.ev_stop && (err = hipEventRecord(c.ev_stop, s)) != hipSuccess) return err;
     }
-    cursor = c.seg[e + 1];
+    for (int e : long_experts) {
+      hipError_t err = run_range(cursor, c.seg[e]);
+      if (err != hipSuccess) return err;
+      cursor = c.seg[e + 1];
+    }
   }
   return run_range(cursor, c.T);
 }

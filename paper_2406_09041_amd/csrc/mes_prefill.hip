@@ -21,16 +21,22 @@ typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 
 constexpr int kMaxWorkgroups = 256;  // one workgroup per compute unit; fewer row groups than that split the contraction
 
+constexpr int kMaxSegs = 8;          // long segments (experts) served by one launch
+
 struct PrefillParams {
   const u32x4* base;        // tiled base weight: block (chunk c, row tile jt) = [4 k blocks][64 lanes] x 16 bytes
-  const uint32_t* codes;    // packed codes: block (c, jt) = 64 * bits words
-  const float* step;        // [d_out]
-  const u32x4* sal;         // salient tile: ((jt * n_sb + sb) * 64 + lane) x 8 fp16
-  const u32x4* xt;          // the segment's activations in fragment order: [k block][token tile][64 lanes] x 16 bytes,
+  // per segment (= per expert with a long segment), n_seg of them:
+  const uint32_t* codes[kMaxSegs];   // packed codes: block (c, jt) = 64 * bits words
+  const float* step[kMaxSegs];       // [d_out]
+  const u32x4* sal[kMaxSegs];        // salient tile: ((jt * n_sb + sb) * 64 + lane) x 8 fp16
+  int t_begin[kMaxSegs], t_end[kMaxSegs];   // the segment's rows of x and y
+  int tb0[kMaxSegs + 1];             // its first token block (of 256 tokens) in the launch; tb0[n_seg] = all blocks
+  int n_seg;
+  const u32x4* xt;          // the segments' activations in fragment order: [k block][token tile][64 lanes] x 16 bytes,
                             // k blocks 0 .. 4 n_chunks - 1 the input channels, then 4 n_ssteps blocks of gathered salient ones
   uint16_t* y;              // bf16 [T, d_out]
   f32x4* tiles;             // split contraction only: accumulator tiles, [split][row group][token block][16 tiles][thread]
-  int d_out, n_jt, n_chunks, n_sb, n_ssteps, n_tq, t_begin, t_end, steps_per_split, n_split;
+  int d_out, n_jt, n_chunks, n_sb, n_ssteps, n_tq, steps_per_split, n_split;
   float z;
 };
 
@@ -49,37 +55,49 @@ __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-// x rows [t_begin, t_end) -> fragment order.  Block (kbi, tq), lane l: token t_begin + 16 tq + (l & 15); for
-// kbi < n_kb_main the 8 input channels 32 kbi + 8 (l >> 4) .., else the 8 salient channels of ranks
-// 32 (kbi - n_kb_main) + 8 (l >> 4) ..; zero beyond the last token, channel or rank.
-__global__ void k_prefill_tile_x(const uint16_t* __restrict__ x, const int32_t* __restrict__ sidx, int k, int t_begin,
-                                 int t_end, int d_in, int n_kb_main, int n_tq, size_t n_blk, u32x4* __restrict__ xt) {
+struct TileParams {
+  const uint16_t* x;
+  const int32_t* sidx[kMaxSegs];
+  int t_begin[kMaxSegs], t_end[kMaxSegs], tb0[kMaxSegs + 1];
+  int n_seg, k, d_in, n_kb_main, n_tq;
+  size_t n_blk;
+  u32x4* xt;
+};
+
+// The segments' rows of x -> fragment order.  Block (kbi, tq), lane l: token 16 tq' + (l & 15) of the segment that
+// token tile tq belongs to (tq' counted from the segment's first tile); for kbi < n_kb_main the 8 input channels
+// 32 kbi + 8 (l >> 4) .., else the 8 salient channels of that segment's expert with ranks
+// 32 (kbi - n_kb_main) + 8 (l >> 4) ..; zero beyond the segment's last token, the last channel or rank.
+__global__ void k_prefill_tile_x(const TileParams p) {
   const int lane = threadIdx.x & 63;
   const size_t blk = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (blk >= n_blk) return;
-  const int tq = (int)(blk % n_tq), kbi = (int)(blk / n_tq);
-  const int t = t_begin + 16 * tq + (lane & 15);
+  if (blk >= p.n_blk) return;
+  const int tq = (int)(blk % p.n_tq), kbi = (int)(blk / p.n_tq);
+  int sg = 0;
+  while (sg + 1 < p.n_seg && tq >= 16 * p.tb0[sg + 1]) ++sg;
+  const int t = p.t_begin[sg] + 16 * (tq - 16 * p.tb0[sg]) + (lane & 15);
   u32x4 v = {0, 0, 0, 0};
-  if (t < t_end) {
-    const uint16_t* row = x + (size_t)t * d_in;
-    if (kbi < n_kb_main) {
+  if (t < p.t_end[sg]) {
+    const uint16_t* row = p.x + (size_t)t * p.d_in;
+    if (kbi < p.n_kb_main) {
       const int c = 32 * kbi + 8 * (lane >> 4);
-      if (c < d_in) v = *reinterpret_cast<const u32x4*>(row + c);
+      if (c < p.d_in) v = *reinterpret_cast<const u32x4*>(row + c);
     } else {
-      const int r0 = 32 * (kbi - n_kb_main) + 8 * (lane >> 4);
+      const int r0 = 32 * (kbi - p.n_kb_main) + 8 * (lane >> 4);
+      const int32_t* sidx = p.sidx[sg];
       uint32_t h[8];
 #pragma unroll
       for (int q = 0; q < 8; ++q) {
         h[q] = 0;
-        if (r0 + q < k) {
+        if (r0 + q < p.k) {
           const int c = sidx[r0 + q];
-          if (c >= 0 && c < d_in) h[q] = row[c];   // a corrupt list can never address outside the row
+          if (c >= 0 && c < p.d_in) h[q] = row[c];   // a corrupt list can never address outside the row
         }
       }
       v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
     }
   }
-  xt[blk * 64 + lane] = v;
+  p.xt[blk * 64 + lane] = v;
 }
 
 // What a builder keeps in flight for one step (128 input channels, or 128 salient ranks) of its row tile.
@@ -90,7 +108,9 @@ struct StepData {
 };
 
 // Grid: (row groups of 16 RT output channels, token blocks of 64 NM tokens, n_split); NM + RT wavefronts in two
-// roles, spread evenly over the SIMDs:
+// roles, spread evenly over the SIMDs.  The token blocks of up to 8 long segments (each with its own expert's codes,
+// steps and salient values) share one launch, so that the compute units go from one expert's work to the next
+// without a launch in between:
 //   builders (the last RT wavefronts): builder r forms the operand of row tile r (16 output channels) for the next
 //     step of 128 input channels in the idle LDS buffer, from base weight and codes requested two steps ahead;
 //   multipliers (wavefronts 0 .. NM - 1): every one multiplies all RT row tiles of the current step (from LDS) with
@@ -114,6 +134,8 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
   const int n_steps = p.n_chunks + p.n_ssteps;
   const int st0 = blockIdx.z * p.steps_per_split;
   const int st1 = st0 + p.steps_per_split < n_steps ? st0 + p.steps_per_split : n_steps;
+  int sg = 0;                                            // the segment (expert) this token block belongs to
+  while (sg + 1 < p.n_seg && (int)blockIdx.y >= p.tb0[sg + 1]) ++sg;
 
   if (wave >= NM) {
     // ---- builder
@@ -121,7 +143,7 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
     int jt = RT * blockIdx.x + rt;                       // stored matrices are padded to whole groups of 4 row tiles:
     jt = jt < p.n_jt ? jt : p.n_jt - 1;                  // a last group of 8 may repeat tiles (its rows are never stored)
     const int row = 16 * jt + n < p.d_out ? 16 * jt + n : p.d_out - 1;
-    const float s = p.step[row];
+    const float s = p.step[sg][row];
     const float zs = p.z * s;
     StepData<BITS> sd[2];
     // Straight-line on purpose (addresses are selected, not branched on): the compiler then knows exactly which
@@ -131,13 +153,13 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
       StepData<BITS>& d = sd[slot];
       const bool main_step = st < p.n_chunks;
       const size_t blk = (size_t)(main_step ? st : p.n_chunks - 1) * p.n_jt + jt;   // a salient step re-reads code words it never uses
-      const uint32_t* cw = p.codes + blk * (64 * BITS);
+      const uint32_t* cw = p.codes[sg] + blk * (64 * BITS);
       const int ss = main_step ? 0 : st - p.n_chunks;
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb) {
         int sb = 4 * ss + kb;
         sb = sb < p.n_sb ? sb : p.n_sb - 1;              // past the last salient block: repeated, zeroed in build()
-        const u32x4* src = main_step ? p.base + (blk * 4 + kb) * 64 : p.sal + ((size_t)jt * p.n_sb + sb) * 64;
+        const u32x4* src = main_step ? p.base + (blk * 4 + kb) * 64 : p.sal[sg] + ((size_t)jt * p.n_sb + sb) * 64;
         d.w[kb] = src[lane];
         const int cl = 16 * kb + n;                      // the code block's lane cl owns columns 32 kb + 8 g + 0..7
         if constexpr (BITS == 1) {
@@ -274,8 +296,8 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
     if (j >= p.d_out) continue;                          // d_out % 4 == 0
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      const int t = p.t_begin + 16 * (tq0 + tt) + n;
-      if (t < p.t_end) {
+      const int t = p.t_begin[sg] + 16 * (tq0 - 16 * p.tb0[sg] + tt) + n;
+      if (t < p.t_end[sg]) {
         const f32x4 o = acc[rt][tt];
         uint2 pk;
         pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
@@ -299,8 +321,10 @@ __global__ __launch_bounds__(64 * NM) void k_prefill_reduce(const PrefillParams 
   for (int sp = 0; sp < p.n_split; ++sp)
     o += p.tiles[((((size_t)sp * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * (RT * TT) + blockIdx.z) * NT + threadIdx.x];
   const int j = 16 * (RT * blockIdx.x + rt) + 4 * g;
-  const int t = p.t_begin + 16 * (TT * (NM * blockIdx.y + wave) + tt) + n;
-  if (j < p.d_out && t < p.t_end) {
+  int sg = 0;
+  while (sg + 1 < p.n_seg && (int)blockIdx.y >= p.tb0[sg + 1]) ++sg;
+  const int t = p.t_begin[sg] + 16 * (TT * (NM * ((int)blockIdx.y - p.tb0[sg]) + wave) + tt) + n;
+  if (j < p.d_out && t < p.t_end[sg]) {
     uint2 pk;
     pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
     pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
@@ -313,12 +337,12 @@ struct PrefillPlan {
   size_t xt_bytes, tiles_at, tiles_bytes;
 };
 
-PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tok) {
+// n_tb: token blocks of all the segments of the launch together
+PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tb) {
   PrefillPlan pl;
   pl.rt = 8;   // 128 rows x 256 tokens per workgroup: measured 6 % faster than 64 x 512 and 14 % faster than 64 x 256
   pl.nm = 4;
-  const int per_wg = 64 * pl.nm;
-  pl.n_tb = (n_tok + per_wg - 1) / per_wg;
+  pl.n_tb = n_tb;
   pl.n_tq = pl.n_tb * 4 * pl.nm;
   pl.n_rg = (ceil_to(d_out, kRowPad) / 16 + pl.rt - 1) / pl.rt;
   pl.n_chunks = ceil_to(d_in, kColPad) / 128;
@@ -344,62 +368,81 @@ hipError_t launch_fused(const PrefillParams& p, const PrefillPlan& pl, dim3 grid
 
 }  // namespace
 
-// Scratch for one segment of up to max_tokens tokens: the activations in fragment order (input channels, then up to
-// d_in gathered salient ones) and, for a split contraction, the accumulator tiles: a split happens only while
-// splits x row groups x token blocks stays within 256 workgroups (plus rounding), each leaving 64 rows x 512 tokens
-// x 4 bytes at most.
+// Scratch for the long segments of a call of up to max_tokens tokens: their activations in fragment order (input
+// channels, then up to d_in gathered salient ones; every segment padded to whole blocks of 256 tokens, at most
+// max_tokens / 192 segments) and, for a split contraction, the accumulator tiles: a split happens only while
+// splits x row groups x token blocks stays within 256 workgroups, each leaving 128 rows x 256 tokens x 4 bytes.
 size_t prefill_scratch_bytes(int d_in, int max_tokens) {
-  const size_t tok_pad = (size_t)((max_tokens + 511) / 512) * 512;
+  const size_t tok_pad = (size_t)max_tokens + (size_t)256 * (max_tokens / 192 + 1);
   const size_t xt = tok_pad * (size_t)(ceil_to(d_in, kColPad) + ceil_to(ceil_to(d_in, kSalPad), 128)) * 2;
-  const size_t tiles = (size_t)2 * kMaxWorkgroups * 64 * 512 * 4;
+  const size_t tiles = (size_t)2 * kMaxWorkgroups * 128 * 256 * 4;
   return (xt + 255) / 256 * 256 + tiles;
 }
 
-// y[rows t_begin .. t_end) of one linear for ONE expert.  scratch: prefill_scratch_bytes(d_in, >= t_end - t_begin).
-hipError_t launch_prefill_segment(const void* w_base_tiled, const mes_delta& d, const void* x, int t_begin, int t_end,
-                                  void* y, void* scratch, hipStream_t s) {
-  const int n_tok = t_end - t_begin;
-  if (n_tok <= 0) return hipSuccess;
-  const PrefillPlan pl = prefill_plan(d.d_in, d.d_out, d.k, n_tok);
+// y rows of the n_seg long segments seg_experts[i] (expert numbers; rows seg[e] .. seg[e + 1]) of one linear, each with
+// its own expert's delta, up to kMaxSegs per launch.  scratch: prefill_scratch_bytes(d_in, >= all their tokens).
+hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
+                                   const int32_t* seg, const void* x, void* y, void* scratch, hipStream_t s) {
   char* ws = reinterpret_cast<char*>(scratch);
-  PrefillParams p;
-  p.base = reinterpret_cast<const u32x4*>(w_base_tiled);
-  p.codes = reinterpret_cast<const uint32_t*>(d.codes);
-  p.step = d.step;
-  p.sal = reinterpret_cast<const u32x4*>(d.salient);
-  p.xt = reinterpret_cast<const u32x4*>(ws);
-  p.y = reinterpret_cast<uint16_t*>(y);
-  p.tiles = reinterpret_cast<f32x4*>(ws + pl.tiles_at);
-  p.d_out = d.d_out;
-  p.n_jt = ceil_to(d.d_out, kRowPad) / 16;
-  p.n_chunks = pl.n_chunks;
-  p.n_sb = ceil_to(d.k, kSalPad) / 32;
-  p.n_ssteps = pl.n_ssteps;
-  p.n_tq = pl.n_tq;
-  p.t_begin = t_begin;
-  p.t_end = t_end;
-  p.steps_per_split = pl.steps_per_split;
-  p.n_split = pl.n_split;
-  p.z = d.grid == MES_GRID_SYM ? (float)(1 << (d.bits - 1)) - 0.5f : (float)(1 << (d.bits - 1));
-  const size_t n_blk = (size_t)4 * (pl.n_chunks + pl.n_ssteps) * pl.n_tq;
-  k_prefill_tile_x<<<(unsigned)((n_blk + 3) / 4), 256, 0, s>>>(reinterpret_cast<const uint16_t*>(x), d.salient_idx, d.k, t_begin,
-                                                                t_end, d.d_in, 4 * pl.n_chunks, pl.n_tq, n_blk,
-                                                                reinterpret_cast<u32x4*>(ws));
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const dim3 grid(pl.n_rg, pl.n_tb, pl.n_split);
-  switch (d.bits) {
-    case 1: e = launch_fused<1>(p, pl, grid, s); break;
-    case 2: e = launch_fused<2>(p, pl, grid, s); break;
-    case 3: e = launch_fused<3>(p, pl, grid, s); break;
-    default: e = launch_fused<4>(p, pl, grid, s); break;
+  for (int first = 0; first < n_seg; first += kMaxSegs) {
+    const int ns = n_seg - first < kMaxSegs ? n_seg - first : kMaxSegs;
+    const mes_delta& d = experts[seg_experts[first]];   // shape, bits, grid and k are the same for all experts of a linear
+    PrefillParams p;
+    TileParams tp;
+    int n_tb = 0;
+    for (int i = 0; i < kMaxSegs; ++i) {
+      const mes_delta& de = experts[seg_experts[first + (i < ns ? i : 0)]];
+      const int e = seg_experts[first + (i < ns ? i : 0)];
+      p.codes[i] = reinterpret_cast<const uint32_t*>(de.codes);
+      p.step[i] = de.step;
+      p.sal[i] = reinterpret_cast<const u32x4*>(de.salient);
+      tp.sidx[i] = de.salient_idx;
+      p.t_begin[i] = tp.t_begin[i] = seg[e];
+      p.t_end[i] = tp.t_end[i] = seg[e + 1];
+      p.tb0[i] = tp.tb0[i] = n_tb;
+      if (i < ns) n_tb += (seg[e + 1] - seg[e] + 255) / 256;
+    }
+    p.tb0[kMaxSegs] = tp.tb0[kMaxSegs] = n_tb;
+    for (int i = ns; i <= kMaxSegs; ++i) p.tb0[i] = tp.tb0[i] = n_tb;
+    p.n_seg = tp.n_seg = ns;
+    const PrefillPlan pl = prefill_plan(d.d_in, d.d_out, d.k, n_tb);
+    p.base = reinterpret_cast<const u32x4*>(w_base_tiled);
+    p.xt = reinterpret_cast<const u32x4*>(ws);
+    p.y = reinterpret_cast<uint16_t*>(y);
+    p.tiles = reinterpret_cast<f32x4*>(ws + pl.tiles_at);
+    p.d_out = d.d_out;
+    p.n_jt = ceil_to(d.d_out, kRowPad) / 16;
+    p.n_chunks = pl.n_chunks;
+    p.n_sb = ceil_to(d.k, kSalPad) / 32;
+    p.n_ssteps = pl.n_ssteps;
+    p.n_tq = pl.n_tq;
+    p.steps_per_split = pl.steps_per_split;
+    p.n_split = pl.n_split;
+    p.z = d.grid == MES_GRID_SYM ? (float)(1 << (d.bits - 1)) - 0.5f : (float)(1 << (d.bits - 1));
+    tp.x = reinterpret_cast<const uint16_t*>(x);
+    tp.k = d.k;
+    tp.d_in = d.d_in;
+    tp.n_kb_main = 4 * pl.n_chunks;
+    tp.n_tq = pl.n_tq;
+    tp.n_blk = (size_t)4 * (pl.n_chunks + pl.n_ssteps) * pl.n_tq;
+    tp.xt = reinterpret_cast<u32x4*>(ws);
+    k_prefill_tile_x<<<(unsigned)((tp.n_blk + 3) / 4), 256, 0, s>>>(tp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const dim3 grid(pl.n_rg, pl.n_tb, pl.n_split);
+    switch (d.bits) {
+      case 1: e = launch_fused<1>(p, pl, grid, s); break;
+      case 2: e = launch_fused<2>(p, pl, grid, s); break;
+      case 3: e = launch_fused<3>(p, pl, grid, s); break;
+      default: e = launch_fused<4>(p, pl, grid, s); break;
+    }
+    if (e != hipSuccess) return e;
+    if (pl.n_split > 1) {
+      k_prefill_reduce<8, 4><<<dim3(grid.x, grid.y, 32), 256, 0, s>>>(p);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
-  if (e != hipSuccess) return e;
-  if (pl.n_split > 1) {
-    k_prefill_reduce<8, 4><<<dim3(grid.x, grid.y, 32), 256, 0, s>>>(p);
-    e = hipGetLastError();
-  }
-  return e;
+  return hipSuccess;
 }
 
 }  // namespace mes

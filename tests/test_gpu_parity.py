@@ -398,6 +398,8 @@ def test_on_demand_swapping_gives_the_resident_result():
                                                            # steps; 136 rows: the second row group is half padding
     (1280, 72, [0, 300, 600], 40, 3, 1),                   # two long segments, few rows: the contraction is split 3 ways
     (2048, 520, [0, 513], 64, 4, 0),                       # 513 tokens (a ragged third token block), 4 bits
+    (264, 72, [0, 200, 205, 405, 605, 805, 1005, 1205, 1405, 1605, 1805, 1810, 2010, 2300], 5, 2, 0),
+                                                           # 11 long segments: two launches of the fused kernel (8 + 3)
 ])
 def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
     """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T by the fused one-product kernel (the
