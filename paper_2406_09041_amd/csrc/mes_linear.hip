@@ -1107,10 +1107,12 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   };   // run_range
 
   // Long expert segments go to the one-product path, everything between them to the streaming path.
-  int longest = 0;
-  for (int e = 0; e < c.n_experts; ++e) longest = c.seg[e + 1] - c.seg[e] > longest ? c.seg[e + 1] - c.seg[e] : longest;
+  // (their activations are re-tiled into the scratch together: it must hold all the long segments' tokens)
+  int long_tokens = 0;
+  for (int e = 0; e < c.n_experts; ++e)
+    if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_tokens += c.seg[e + 1] - c.seg[e];
   const size_t scratch_at = (wl.total + 255) / 256 * 256;
-  const bool can_prefill = longest >= kPrefillMin && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, longest);
+  const bool can_prefill = long_tokens > 0 && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, long_tokens);
   // the long segments of every linear in one go (up to 8 experts per launch), then the streaming ranges between them
   int cursor = 0;
   if (can_prefill) {

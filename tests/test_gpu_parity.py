@@ -420,6 +420,21 @@ def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid
     assert rel_fro(y, y_stream.double().cpu().numpy()) <= 4e-3
 
 
+def test_long_segments_with_a_workspace_sized_for_fewer_tokens():
+    """All long segments of a call are re-tiled into the scratch together.  A workspace sized for 512 tokens serves a
+    call with one 300-token segment on the one-product path and keeps a call with three of them (900 tokens of long
+    segments) on the streaming path; both must match the oracle."""
+    d_in, d_out = 392, 136
+    ws = mes.make_workspace(d_in, d_out, 512, torch.device(DEV))
+    for seg in ([0, 5, 305, 330], [0, 300, 600, 900, 910]):
+        wl = synth.small_case(d_in, d_out, seg, 6, 2, seed=600 + len(seg))
+        w_t = mes.mes_pack_base(wl.w_base.to(DEV))
+        y = mes.mes_delta_linear(w_t, gpu_experts(wl), wl.x.to(DEV), wl.seg_offsets, workspace=ws)
+        torch.cuda.synchronize()
+        y_ref = O.delta_linear(wl.x.double().numpy(), wl.w_base.double().numpy(), oracle_experts(wl), wl.seg_offsets)
+        assert rel_fro(y, y_ref) <= TOL
+
+
 def test_long_segments_in_a_fused_call():
     d_in, seg = 512, [0, 4, 210, 230]
     wls = [synth.small_case(d_in, d, seg, 8, 2, seed=400 + i) for i, d in enumerate([128, 72])]
