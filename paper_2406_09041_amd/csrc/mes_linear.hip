@@ -38,8 +38,6 @@
 // where a run-time slot number can index them.
 #include "mes_internal.h"
 
-#include <vector>
-
 #ifdef MES_TRACE
 #include <cstdio>
 #include <cstdlib>
@@ -1116,19 +1114,20 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   // the long segments of every linear in one go (up to 8 experts per launch), then the streaming ranges between them
   int cursor = 0;
   if (can_prefill) {
-    std::vector<int> long_experts;
+    int long_experts[MES_MAX_EXPERTS], n_long = 0;
     for (int e = 0; e < c.n_experts; ++e)
-      if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_experts.push_back(e);
+      if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_experts[n_long++] = e;
     for (int l = 0; l < c.n_linears; ++l) {
       hipError_t err;
       if (c.ev_start && first_kernel && (err = hipEventRecord(c.ev_start, s)) != hipSuccess) return err;
       first_kernel = false;
-      err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts.data(), (int)long_experts.size(),
-                                    c.seg, c.x, c.lin[l].y, ws + scratch_at, s);
+      err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts, n_long, c.seg, c.x, c.lin[l].y,
+                                    ws + scratch_at, s);
       if (err != hipSuccess) return err;
       if (c.ev_stop && (err = hipEventRecord(c.ev_stop, s)) != hipSuccess) return err;
     }
-    for (int e : long_experts) {
+    for (int i = 0; i < n_long; ++i) {
+      const int e = long_experts[i];
       hipError_t err = run_range(cursor, c.seg[e]);
       if (err != hipSuccess) return err;
       cursor = c.seg[e + 1];
