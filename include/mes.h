@@ -113,6 +113,7 @@ size_t mes_select_workspace_bytes(int n, int d_in, int d_out);
  * which for long segments is several times faster than streaming the weights once per 64 tokens.  A workspace
  * sized with a smaller max_tokens is accepted by every call and keeps it on the streaming path. */
 size_t mes_linear_workspace_bytes(int d_in, int d_out, int max_tokens);
+int mes_long_segment_tokens(void);   /* the segment length from which the one-product path is taken (192) */
 size_t mes_linear_multi_workspace_bytes(int d_in, const int32_t* d_out /*HOST [n_linears]*/, int n_linears, int max_tokens);
 const char* mes_last_error(void);
 int mes_layout_version(void);
@@ -184,15 +185,6 @@ mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, 
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream);
 
-/* Measurement hook (for benchmarks; the latency analysis of Section 5.2 times the layer, this times its dominant
- * kernel): the NEXT mes_delta_linear / mes_delta_linear_multi call of the calling thread records `start_event`
- * on its stream immediately before its first streaming kernel and `stop_event` immediately after its last one
- * (hipEvent_t passed as void*, HOST handles owned by the caller).  A call whose batch fits one token group
- * (at most 64 tokens routed to at most 16 experts) has exactly one streaming
- * kernel between the two; a larger batch also has the helper kernels of the later groups in between.
- * One-shot; two NULLs cancel. */
-mes_status mes_time_next_call(void* start_event, void* stop_event);
-
 /* ---- on-demand swapping (Section 4.1, "On-demand swapping": the base model stays on the GPU, the compressed
  * deltas of the experts a batch needs are loaded when they are needed) ----------------------------------------
  * A pool serves ONE linear layer.  It owns nothing but its bookkeeping: the caller gives it a DEVICE arena of
@@ -237,8 +229,7 @@ mes_status mes_pool_stats(const mes_pool* pool, uint64_t* hits, uint64_t* misses
  * delta: fp32 [d_out, d_in], 16-byte aligned.  salient_idx: int32 [k] ascending as for mes_pack_delta (entries
  * outside [0, d_in) are ignored), NULL if k = 0.  step: fp32 [d_out], 16-byte aligned; rows whose step is not > 0
  * report loss 0 and grad 0.  loss_out, grad_out: fp32 [d_out], fully overwritten.  n_tokens >= 0.
- * workspace >= mes_step_grad_workspace_bytes(d_in, d_out, n_tokens), 16-byte aligned.  Never synchronises.
- * mes_time_next_call applies: the events bracket the one kernel that does the contractions. */
+ * workspace >= mes_step_grad_workspace_bytes(d_in, d_out, n_tokens), 16-byte aligned.  Never synchronises. */
 size_t mes_step_grad_workspace_bytes(int d_in, int d_out, int n_tokens);
 mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t* salient_idx, int k, int bits, int grid,
                          const float* step, const void* x, int n_tokens, float* loss_out, float* grad_out,
@@ -250,12 +241,6 @@ mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t*
  * number of this update.  step, grad, m, v: DEVICE fp32 [n]; m and v start at 0. */
 mes_status mes_step_adamw(float* step, const float* grad, float* m, float* v, int n, int t, float lr, float beta1,
                           float beta2, float eps, float weight_decay, void* stream);
-
-/* Measurement hook: a plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers DEVICE,
- * 16-byte aligned, not overlapping) done by one kernel, k_copy_probe.  It reads and writes exactly `bytes`
- * of HBM, which is what a profiler's memory-traffic counters are scaled by before they are compared with the
- * streaming kernel's algorithmic bytes. */
-mes_status mes_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

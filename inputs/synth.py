@@ -184,6 +184,38 @@ def config4_linear(which: str, device: str = "cpu", layer: int = 0, n_tokens: in
                        device=device, shape_id=sid, x_id=(0 if d_in == 4096 else 1))
 
 
+def config5_routing(part: str = "mixed", n_decode: int = 256, n_prefill: int = 4,
+                    prefill_len: int = 1024, n_experts: int = 16):
+    """Routing of the mixed batch of the 32-layer configuration: `n_decode` decode tokens with iid Zipf(1.1) expert
+    ids and `n_prefill` prompt sequences of `prefill_len` tokens, each sequence routed as a whole to one
+    Zipf-drawn expert; tokens sorted by expert (an expert's decode tokens first, then its sequences).  The
+    method routes a query to one expert MODEL, so every layer of the stack sees this same routing.
+    part = "decode" / "prefill" keeps only that kind of token, with the same draws.  Returns seg_offsets."""
+    dec = zipf_expert_ids(n_decode, n_experts, 1.1, seed_for(5, 0, 0, 9))
+    pre = zipf_expert_ids(n_prefill, n_experts, 1.1, seed_for(5, 0, 0, 10))
+    counts = torch.zeros(n_experts, dtype=torch.int64)
+    if part in ("mixed", "decode"):
+        counts += torch.bincount(dec, minlength=n_experts)
+    if part in ("mixed", "prefill"):
+        counts += prefill_len * torch.bincount(pre, minlength=n_experts)
+    off = [0]
+    for c in counts.tolist():
+        off.append(off[-1] + int(c))
+    return off
+
+
+def config5_linear(which: str, layer: int = 0, bits: int = 2, device: str = "cpu", part: str = "mixed",
+                   k: int = 64, n_experts: int = 16) -> LinearWorkload:
+    """One linear of one layer of the 32-layer stack: a Mistral-7B shape, 16 experts, the mixed batch of
+    config5_routing (256 decode tokens + 4 x 1024 prompt tokens).  Weights and deltas depend on (layer, shape,
+    expert); the activations only on the input width, so layers of one width read one batch."""
+    shapes = {n: (i, di, do) for i, (n, di, do) in enumerate(MISTRAL7B_LINEARS)}
+    sid, d_in, d_out = shapes[which]
+    off = config5_routing(part, n_experts=n_experts)
+    return make_linear(f"c5_{which}_L{layer}", d_in, d_out, n_experts, off, k, bits, 5, layer=layer,
+                       device=device, shape_id=sid, x_id=(0 if d_in == 4096 else 1))
+
+
 def small_case(d_in: int, d_out: int, seg_offsets: Sequence[int], k: int, bits: int,
                seed: int = 0, device: str = "cpu", **kw) -> LinearWorkload:
     """Free-form small case for parity tests (ragged shapes, empty segments, ...)."""

@@ -30,7 +30,7 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
            "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
            "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
-           "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw"]
+           "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_long_segment_tokens"]
 
 
 class MesError(RuntimeError):
@@ -86,6 +86,8 @@ def _load() -> ctypes.CDLL:
     lib.mes_delta_linear.restype = c_int
     lib.mes_delta_linear.argtypes = [vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
                                      ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
+    lib.mes_long_segment_tokens.restype = c_int
+    lib.mes_long_segment_tokens.argtypes = []
     lib.mes_linear_multi_workspace_bytes.restype = c_sz
     lib.mes_linear_multi_workspace_bytes.argtypes = [c_int, ctypes.POINTER(ctypes.c_int32), c_int, c_int]
     lib.mes_delta_linear_multi.restype = c_int
@@ -151,7 +153,7 @@ def mes_pack_base(w: torch.Tensor) -> torch.Tensor:
 
 
 def mes_copy_probe(dst: torch.Tensor, src: torch.Tensor) -> None:
-    """Plain copy kernel of known traffic (src.nbytes read, as many written); see mes_copy_probe in mes.h."""
+    """Plain copy kernel of known traffic (src.nbytes read, as many written); see mes_copy_probe in mes_bench.h."""
     assert dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous() and dst.nbytes == src.nbytes
     _check(lib.mes_copy_probe(_ptr(dst), _ptr(src), src.nbytes, _stream(src.device)))
 
@@ -307,8 +309,9 @@ def mes_delta_linear_descriptors(w_base_tiled: torch.Tensor, desc, x: torch.Tens
 class DeltaLinearMulti:
     """Marshalled arguments of mes_delta_linear_multi: several layers that read the same activations and routing."""
 
-    def __init__(self, layers: Sequence, max_tokens: int = 64):
-        """layers: sequence of (w_base_tiled, [PackedDelta per expert])."""
+    def __init__(self, layers: Sequence, max_tokens: int = 64, workspace: Optional[torch.Tensor] = None):
+        """layers: sequence of (w_base_tiled, [PackedDelta per expert]).  workspace: an initialised workspace of at
+        least workspace_bytes(...) bytes to share between calls that are stream-ordered, or None to allocate one."""
         self.ws_tiled = [w for w, _ in layers]
         self.experts = [list(ex) for _, ex in layers]
         self.n = len(layers)
@@ -319,8 +322,17 @@ class DeltaLinearMulti:
         dev = self.ws_tiled[0].device
         d = (ctypes.c_int32 * self.n)(*self.d_out)
         nbytes = max(lib.mes_linear_multi_workspace_bytes(self.d_in, d, self.n, max_tokens), 16)
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        _check(lib.mes_workspace_init(_ptr(self.ws), nbytes, _stream(dev)))
+        if workspace is not None:
+            assert workspace.numel() >= nbytes
+            self.ws = workspace
+        else:
+            self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            _check(lib.mes_workspace_init(_ptr(self.ws), nbytes, _stream(dev)))
+
+    @staticmethod
+    def workspace_bytes(d_in: int, d_outs: Sequence[int], max_tokens: int) -> int:
+        d = (ctypes.c_int32 * len(d_outs))(*d_outs)
+        return max(lib.mes_linear_multi_workspace_bytes(d_in, d, len(d_outs), max_tokens), 16)
 
     def __call__(self, x: torch.Tensor, seg_offsets: Sequence[int], ys: Optional[Sequence[torch.Tensor]] = None):
         T = x.shape[0]
@@ -400,25 +412,31 @@ class ExpertPool:
 
 
 class KernelTimer:
-    """HIP events recorded by the library around its streaming kernel (mes_time_next_call)."""
+    """HIP events recorded by the library around its dominant kernel (mes_time_next_call in mes_bench.h): `n` pairs,
+    so that a whole sequence of calls can be timed without a synchronisation in between."""
 
-    def __init__(self):
+    def __init__(self, n: int = 1):
         self.hip = ctypes.CDLL("libamdhip64.so")
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-        self.start, self.stop = ctypes.c_void_p(), ctypes.c_void_p()
-        for ev in (self.start, self.stop):
-            if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
-                raise RuntimeError("hipEventCreate failed")
+        self.pairs = []
+        for _ in range(n):
+            pair = (ctypes.c_void_p(), ctypes.c_void_p())
+            for ev in pair:
+                if self.hip.hipEventCreate(ctypes.byref(ev)) != 0:
+                    raise RuntimeError("hipEventCreate failed")
+            self.pairs.append(pair)
 
-    def arm(self) -> None:
-        _check(lib.mes_time_next_call(self.start, self.stop))
+    def arm(self, i: int = 0) -> None:
+        """The next timed library call of this thread records pair i."""
+        _check(lib.mes_time_next_call(self.pairs[i][0], self.pairs[i][1]))
 
-    def elapsed_us(self) -> float:
-        if self.hip.hipEventSynchronize(self.stop) != 0:
+    def elapsed_us(self, i: int = 0) -> float:
+        start, stop = self.pairs[i]
+        if self.hip.hipEventSynchronize(stop) != 0:
             raise RuntimeError("hipEventSynchronize failed")
         ms = ctypes.c_float()
-        if self.hip.hipEventElapsedTime(ctypes.byref(ms), self.start, self.stop) != 0:
+        if self.hip.hipEventElapsedTime(ctypes.byref(ms), start, stop) != 0:
             raise RuntimeError("hipEventElapsedTime failed")
         return ms.value * 1e3

@@ -1,5 +1,6 @@
 // extern "C" entry points: argument validation on the host (before any HIP call), then launch.
 #include "mes_internal.h"
+#include "mes_bench.h"
 
 #include <cstdarg>
 #include <cstdio>
@@ -49,6 +50,7 @@ extern "C" {
 
 const char* mes_last_error(void) { return g_err; }
 int mes_layout_version(void) { return MES_LAYOUT_VERSION; }
+int mes_long_segment_tokens(void) { return long_segment_tokens(); }
 
 size_t mes_base_bytes(int d_in, int d_out) {
   if (d_in <= 0 || d_out <= 0) return 0;
@@ -172,6 +174,9 @@ mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* str
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream) {
   const char* who = "mes_delta_linear";
+  // the measurement hook is one-shot: this call consumes the events whichever way it returns
+  const hipEvent_t ev_start = g_ev_start, ev_stop = g_ev_stop;
+  g_ev_start = g_ev_stop = nullptr;
   if (n_linears < 1 || n_linears > MES_MAX_FUSED)
     return fail(MES_ERR_SHAPE, "%s: n_linears = %d outside [1, %d]", who, n_linears, MES_MAX_FUSED);
   if (n_experts < 1 || n_experts > MES_MAX_EXPERTS)
@@ -207,8 +212,7 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
   const size_t need = mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, 1);
   if (!workspace || workspace_bytes < need) return fail(MES_ERR_WORKSPACE, "%s: workspace needs %zu bytes", who, need);
   if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "%s: workspace must be 16-byte aligned", who);
-  LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, g_ev_start, g_ev_stop};
-  g_ev_start = g_ev_stop = nullptr;
+  LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, ev_start, ev_stop};
   return check_hip(launch_delta_linear(c, (hipStream_t)stream), who);
 }
 
@@ -234,6 +238,8 @@ size_t mes_step_grad_workspace_bytes(int d_in, int d_out, int n_tokens) {
 mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t* salient_idx, int k, int bits, int grid,
                          const float* step, const void* x, int n_tokens, float* loss_out, float* grad_out,
                          void* workspace, size_t workspace_bytes, void* stream) {
+  const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;   // one-shot measurement hook, consumed on every exit path
+  g_ev_start = g_ev_stop = nullptr;
   if (!delta || !step || !loss_out || !grad_out) return fail(MES_ERR_NULL, "mes_step_grad: null pointer");
   if (mes_status st = check_dims(d_in, d_out)) return st;
   if (mes_status st = check_quant(bits, grid, MES_STEP_GIVEN, true)) return st;
@@ -246,8 +252,6 @@ mes_status mes_step_grad(const float* delta, int d_in, int d_out, const int32_t*
   if (!workspace || workspace_bytes < mes_step_grad_workspace_bytes(d_in, d_out, n_tokens))
     return fail(MES_ERR_WORKSPACE, "mes_step_grad: workspace needs %zu bytes", mes_step_grad_workspace_bytes(d_in, d_out, n_tokens));
   if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "mes_step_grad: workspace must be 16-byte aligned");
-  const hipEvent_t e0 = g_ev_start, e1 = g_ev_stop;
-  g_ev_start = g_ev_stop = nullptr;
   return check_hip(launch_step_grad(delta, d_in, d_out, salient_idx, k, bits, grid, step, x, n_tokens, loss_out, grad_out,
                                     workspace, e0, e1, (hipStream_t)stream), "mes_step_grad");
 }

@@ -45,6 +45,7 @@ struct LinearCall {
   hipEvent_t ev_start, ev_stop;   // measurement hook (nullptr: none)
 };
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens);
+int long_segment_tokens();
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
 
 // ---- implemented in mes_step.hip ---------------------------------------------------------------
@@ -58,6 +59,7 @@ hipError_t launch_adamw(float* step, const float* grad, float* m, float* v, int 
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
 size_t prefill_scratch_bytes(int d_in, int max_tokens);
 hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
-                                   const int32_t* seg, const void* x, void* y, void* scratch, hipStream_t s);
+                                   const int32_t* seg, const void* x, void* y, void* scratch, hipEvent_t ev_start,
+                                   hipEvent_t ev_stop, bool* first_kernel, hipStream_t s);
 
 }  // namespace mes

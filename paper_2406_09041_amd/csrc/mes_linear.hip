@@ -38,10 +38,6 @@
 // where a run-time slot number can index them.
 #include "mes_internal.h"
 
-#ifdef MES_TRACE
-#include <cstdio>
-#include <cstdlib>
-#endif
 
 namespace mes {
 namespace {
@@ -91,9 +87,6 @@ struct LinearParams {
   int tile_first[4], tile_last[4];        // slots that own tokens of 16-token tile tt: tile_first[tt] .. tile_last[tt]
   int d_in, n_linears, n_chunks, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
   float z;
-#ifdef MES_TRACE
-  unsigned long long* trace;   // development builds only: [call][workgroup][16] timestamps
-#endif
 };
 
 // The linear a row group belongs to.
@@ -104,11 +97,6 @@ __device__ __forceinline__ int linear_of(const LinearParams& p, int rg) {
   return l;
 }
 
-#ifdef MES_TRACE
-#define MES_STAMP(i) do { if (threadIdx.x == 0) p.trace[((size_t)(blockIdx.y * gridDim.x + blockIdx.x)) * 16 + (i)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define MES_STAMP(i) do { } while (0)
-#endif
 
 __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -616,16 +604,9 @@ struct Stream {
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
   // NOBASE: a sweep after the first -- the base product is done, only the slots of this sweep are multiplied.
   template <int BUF, bool NOBASE>
-  __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave, bool tr = false) {
-#ifdef MES_TRACE
-#define MES_CSTAMP(i) do { if (tr) MES_STAMP(i); } while (0)
-#else
-#define MES_CSTAMP(i) do { } while (0)
-#endif
-    MES_CSTAMP(2);
+  __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave) {
     stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
     sal_lookup();
-    MES_CSTAMP(3);
     // Order inside a tile: the low-bit visits first (operands bhi / blo, read from LDS during the previous
     // tile's base product), then the base product (operands xb, read while the visits ran).  Every LDS read is
     // thereby issued a good stretch of arithmetic before its data are needed.
@@ -666,7 +647,6 @@ struct Stream {
         for (int kb = 0; kb < 4; ++kb) acc_base[tt] = mfma_bf16(base[BUF][kb], xb[kb], acc_base[tt]);
       }
       if (tt == 0) sal_address();
-      MES_CSTAMP(4 + tt);
     }
     static_assert(kSalPerChunk == 1, "one pair per chunk: the request steps above prepare exactly one");
     sal_multiply(0);
@@ -675,9 +655,7 @@ struct Stream {
     // its visits of this chunk are over, the area is its own, and the wavefronts get here at slightly
     // different times -- the 64 KiB of LDS writes spread out and fill what would be waiting at the barrier.
     park<BUF ^ 1>();
-    MES_CSTAMP(8);
     stage_barrier<younger<NOBASE>()>();
-    MES_CSTAMP(9);
   }
 };
 
@@ -696,7 +674,6 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   jt = live ? jt : L.n_jt - 1;
   const int c_begin = (int)((long)sp * p.n_chunks / p.nsplit);
   const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
-  MES_STAMP(0);
 
   // One LDS block carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
   // offset field of the LDS instructions, so one lane-offset register serves every operand read.
@@ -748,8 +725,6 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   ws.template load_scales<0>(chunk_at(0));
   ws.template load_code_regs<0>(chunk_at(0));
   ws.template load_code_regs<1>(chunk_at(1));
-
-  MES_STAMP(12);
   // What the epilogue needs -- every slot's step for this wavefront's 16 output channels, and per token the
   // zero-point correction and the salient scale -- is fetched now and kept in LDS until then: in registers
   // it would be live across the whole stream.  (The correction belongs to the whole column range: only the
@@ -760,7 +735,6 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   float2 tok_v = {0.0f, 0.0f};
   if (tid < kTokGroup) tok_v = float2{sp == 0 ? L.corr[tid] : 0.0f, L.sal_scale[tid]};
   ws.sal_begin(sp);
-  MES_STAMP(13);
   if (st_a < kLaunchSlots) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
   if (tid < kTokGroup) tok_lds[tid] = tok_v;
 
@@ -778,9 +752,8 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   ws.sal_lookup();
   ws.sal_address();
   ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
-  MES_STAMP(1);
   for (int i = 0; i < len; i += 2) {
-    ws.template chunk<0, false>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave, i == 4);
+    ws.template chunk<0, false>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave);
     if (i + 1 >= len) break;
     ws.template chunk<1, false>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
   }
@@ -837,7 +810,6 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
       *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
     }
   }
-  MES_STAMP(14);
 }
 
 // Split columns only: y = sum over splits (in split order) of the fp32 partial tiles, rounded to bf16.  One
@@ -882,9 +854,6 @@ inline int row_groups_of(int d_out, int nw) { return (ceil_to(d_out, kRowPad) / 
 // among equals, few splits (every split writes and re-reads a partial output tile).
 Plan plan_for(int d_in, const int* d_out, int n_linears) {
   const int n_chunks = ceil_to(d_in, kColPad) / kChunk;
-#ifdef MES_TRACE
-  if (const char* ov = getenv("MES_PLAN")) { Plan o{1, 8}; if (sscanf(ov, "%d,%d", &o.nsplit, &o.nw) >= 1) return o; }
-#endif
   Plan best{1, kMaxWaves};
   double best_cost = 1e30;
   for (int nw = kMaxWaves; nw >= 6; --nw) {
@@ -962,15 +931,12 @@ hipError_t launch_reduce(const LinearParams& p, int tt, int nw, int row_groups, 
 
 }  // namespace
 
-#ifdef MES_TRACE
-unsigned long long* g_trace = nullptr;
-int g_call = 0;
-#endif
 
 // Expert segments at least this long take the one-product path of mes_prefill.hip (W + Delta~ formed in registers,
 // one dense contraction) when the workspace has room for it: from here on it is cheaper than streaming the weights
 // once per 64 tokens.
 constexpr int kPrefillMin = 192;
+int long_segment_tokens() { return kPrefillMin; }
 
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
   size_t n = workspace_layout(d_in, d_out, n_linears).total;   // one 64-token group is in flight at a time
@@ -985,11 +951,6 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   const WorkspaceLayout wl = workspace_layout(d0.d_in, d_outs, c.n_linears);
   char* ws = reinterpret_cast<char*>(c.ws);
   LinearParams p;
-#ifdef MES_TRACE
-  if (!g_trace) { if (hipMalloc(&g_trace, (size_t)64 << 20) != hipSuccess) return hipErrorOutOfMemory; (void)hipMemset(g_trace, 0, (size_t)64 << 20); }
-  p.trace = g_trace + (size_t)(g_call % 64) * (1 << 17);
-  ++g_call;
-#endif
   p.x = reinterpret_cast<const uint16_t*>(c.x);
   p.xt = ws + wl.xt;
   p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
@@ -1118,13 +1079,9 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     for (int e = 0; e < c.n_experts; ++e)
       if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_experts[n_long++] = e;
     for (int l = 0; l < c.n_linears; ++l) {
-      hipError_t err;
-      if (c.ev_start && first_kernel && (err = hipEventRecord(c.ev_start, s)) != hipSuccess) return err;
-      first_kernel = false;
-      err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts, n_long, c.seg, c.x, c.lin[l].y,
-                                    ws + scratch_at, s);
+      hipError_t err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts, n_long, c.seg, c.x,
+                                               c.lin[l].y, ws + scratch_at, c.ev_start, c.ev_stop, &first_kernel, s);
       if (err != hipSuccess) return err;
-      if (c.ev_stop && (err = hipEventRecord(c.ev_stop, s)) != hipSuccess) return err;
     }
     for (int i = 0; i < n_long; ++i) {
       const int e = long_experts[i];
@@ -1138,11 +1095,3 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
 
 }  // namespace mes
 
-#ifdef MES_TRACE
-// Development builds only: copy call slot `slot` (of the last 64 calls) of the timestamp trace to the host.
-extern "C" int mes_debug_trace(int slot, unsigned long long* out, size_t n) {
-  if (!mes::g_trace) return 1;
-  return (int)hipMemcpy(out, mes::g_trace + (size_t)(slot % 64) * (1 << 17), n * sizeof(unsigned long long), hipMemcpyDeviceToHost);
-}
-extern "C" int mes_debug_calls(void) { return mes::g_call; }
-#endif

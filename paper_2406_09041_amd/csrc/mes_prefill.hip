@@ -381,8 +381,11 @@ size_t prefill_scratch_bytes(int d_in, int max_tokens) {
 
 // y rows of the n_seg long segments seg_experts[i] (expert numbers; rows seg[e] .. seg[e + 1]) of one linear, each with
 // its own expert's delta, up to kMaxSegs per launch.  scratch: prefill_scratch_bytes(d_in, >= all their tokens).
+// ev_start / ev_stop (measurement hook, may be null): recorded immediately before the first fused kernel (only while
+// *first_kernel is set, which this clears) and immediately after every fused kernel and its reduction.
 hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
-                                   const int32_t* seg, const void* x, void* y, void* scratch, hipStream_t s) {
+                                   const int32_t* seg, const void* x, void* y, void* scratch, hipEvent_t ev_start,
+                                   hipEvent_t ev_stop, bool* first_kernel, hipStream_t s) {
   char* ws = reinterpret_cast<char*>(scratch);
   for (int first = 0; first < n_seg; first += kMaxSegs) {
     const int ns = n_seg - first < kMaxSegs ? n_seg - first : kMaxSegs;
@@ -430,6 +433,8 @@ hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* ex
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const dim3 grid(pl.n_rg, pl.n_tb, pl.n_split);
+    if (ev_start && *first_kernel && (e = hipEventRecord(ev_start, s)) != hipSuccess) return e;
+    *first_kernel = false;
     switch (d.bits) {
       case 1: e = launch_fused<1>(p, pl, grid, s); break;
       case 2: e = launch_fused<2>(p, pl, grid, s); break;
@@ -441,6 +446,7 @@ hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* ex
       k_prefill_reduce<8, 4><<<dim3(grid.x, grid.y, 32), 256, 0, s>>>(p);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
+    if (ev_stop && (e = hipEventRecord(ev_stop, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }

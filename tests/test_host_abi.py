@@ -17,9 +17,11 @@ ODD = 0x10004           # misaligned
 
 
 def test_every_declared_symbol_is_exported():
-    text = open(os.path.join(ROOT, "include", "mes.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    declared = set(re.findall(r"\b(mes_[a-z_]+)\s*\(", text))
+    declared = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        declared |= set(re.findall(r"\b(mes_[a-z_]+)\s*\(", text))
     assert declared == set(B.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
