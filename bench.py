@@ -508,9 +508,7 @@ def bench_stack(args):
     for g in FUSED_GROUPS:
         d_in, d_outs = shapes[g[0]][0], [shapes[n][1] for n in g]
         nbytes = mes.DeltaLinearMulti.workspace_bytes(d_in, d_outs, T)
-        buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        mes.binding._check(mes.binding.lib.mes_workspace_init(mes.binding._ptr(buf), nbytes, mes.binding._stream(torch.device(dev))))
-        ws["+".join(g)] = buf
+        ws["+".join(g)] = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     ys = {p: {n: torch.empty((parts[p][-1], do), dtype=torch.bfloat16, device=dev) for n, (di, do) in shapes.items()} for p in parts}
     t_setup = time.perf_counter()
     stack, sampler = [], Sampler(4545)

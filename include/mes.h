@@ -153,10 +153,6 @@ mes_status mes_pack_delta(const float* delta, int d_in, int d_out, const int32_t
  * codes_out: uint8 [d_out, d_in] (0xFF at salient columns) or NULL. */
 mes_status mes_unpack_delta(const mes_delta* d, float* delta_hat_out, uint8_t* codes_out, void* stream);
 
-/* Zero a mes_delta_linear workspace.  Call once after allocating it (mes_delta_linear leaves it
- * ready for the next call). */
-mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
-
 /* The hot path (Eq. 4, batched across experts):
  *   y[t] = x[t] W_base^T + step_e .* (x_ns[t] (U_e - z)^T) + x_s[t] D_e^T,   e = expert of row t.
  * w_base_tiled: output of mes_pack_base for [d_out, d_in].
@@ -166,8 +162,8 @@ mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* str
  *    0 = o[0] <= o[1] <= ... <= o[E] = T; rows o[e]..o[e+1] use expert e; an expert with an
  *    empty segment costs no memory traffic.
  * y: bf16 [T, d_out] row-major, fully overwritten (round-to-nearest-even from fp32 accumulators).
- * workspace: >= mes_linear_workspace_bytes(d_in, d_out, T), initialised by mes_workspace_init;
- *    calls sharing a workspace must be stream-ordered.
+ * workspace: >= mes_linear_workspace_bytes(d_in, d_out, T), 16-byte aligned, contents irrelevant (scratch: nothing
+ *    is kept in it between calls); calls sharing a workspace must be stream-ordered.
  * T = 0 returns MES_OK without touching anything.  Enqueues on `stream`, never synchronises. */
 mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, int n_experts,
                             const void* x, int T, const int32_t* seg_offsets, void* y,
@@ -180,7 +176,7 @@ mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, 
  * n_experts expert deltas (with their own salient channels) and its own output; d_out may differ between
  * layers, d_in, k, bits and grid must be the same for all layers and experts.
  * x, T, seg_offsets, stream, T = 0: as for mes_delta_linear.
- * workspace: >= mes_linear_multi_workspace_bytes(d_in, d_out[], n_linears, T), initialised by mes_workspace_init.
+ * workspace: >= mes_linear_multi_workspace_bytes(d_in, d_out[], n_linears, T), as for mes_delta_linear.
  * With n_linears = 1 this is mes_delta_linear. */
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream);

@@ -27,7 +27,7 @@ STATUS_NAMES = {0: "MES_OK", 1: "MES_ERR_NULL", 2: "MES_ERR_SHAPE", 3: "MES_ERR_
 EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_workspace_bytes",
            "mes_select_workspace_bytes", "mes_linear_workspace_bytes", "mes_last_error", "mes_layout_version",
            "mes_pack_base", "mes_unpack_base", "mes_select_salient", "mes_pack_delta", "mes_unpack_delta",
-           "mes_workspace_init", "mes_delta_linear", "mes_linear_multi_workspace_bytes",
+           "mes_delta_linear", "mes_linear_multi_workspace_bytes",
            "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
            "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
            "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_long_segment_tokens"]
@@ -81,8 +81,6 @@ def _load() -> ctypes.CDLL:
     lib.mes_pack_delta.argtypes = [vp, c_int, c_int, vp, c_int, c_int, c_int, c_int, vp, vp, vp, vp, vp, c_sz, vp]
     lib.mes_unpack_delta.restype = c_int
     lib.mes_unpack_delta.argtypes = [ctypes.POINTER(mes_delta), vp, vp, vp]
-    lib.mes_workspace_init.restype = c_int
-    lib.mes_workspace_init.argtypes = [vp, c_sz, vp]
     lib.mes_delta_linear.restype = c_int
     lib.mes_delta_linear.argtypes = [vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
                                      ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
@@ -261,11 +259,9 @@ def mes_step_adamw(step: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: t
 
 
 def make_workspace(d_in: int, d_out: int, max_tokens: int, device) -> torch.Tensor:
-    """Allocates and initialises a mes_delta_linear workspace."""
+    """Allocates a mes_delta_linear workspace (scratch: its contents do not matter)."""
     n = max(linear_workspace_bytes(d_in, d_out, max_tokens), 16)
-    ws = torch.empty(n, dtype=torch.uint8, device=device)
-    _check(lib.mes_workspace_init(_ptr(ws), n, _stream(device)))
-    return ws
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 class DeltaLinear:
@@ -310,7 +306,7 @@ class DeltaLinearMulti:
     """Marshalled arguments of mes_delta_linear_multi: several layers that read the same activations and routing."""
 
     def __init__(self, layers: Sequence, max_tokens: int = 64, workspace: Optional[torch.Tensor] = None):
-        """layers: sequence of (w_base_tiled, [PackedDelta per expert]).  workspace: an initialised workspace of at
+        """layers: sequence of (w_base_tiled, [PackedDelta per expert]).  workspace: a workspace of at
         least workspace_bytes(...) bytes to share between calls that are stream-ordered, or None to allocate one."""
         self.ws_tiled = [w for w, _ in layers]
         self.experts = [list(ex) for _, ex in layers]
@@ -327,7 +323,6 @@ class DeltaLinearMulti:
             self.ws = workspace
         else:
             self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-            _check(lib.mes_workspace_init(_ptr(self.ws), nbytes, _stream(dev)))
 
     @staticmethod
     def workspace_bytes(d_in: int, d_outs: Sequence[int], max_tokens: int) -> int:

@@ -165,12 +165,6 @@ mes_status mes_unpack_delta(const mes_delta* d, float* delta_hat_out, uint8_t* c
   return check_hip(launch_unpack_delta(*d, delta_hat_out, codes_out, (hipStream_t)stream), "mes_unpack_delta");
 }
 
-mes_status mes_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
-  if (!workspace) return fail(MES_ERR_NULL, "mes_workspace_init: null workspace");
-  if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "mes_workspace_init: workspace must be 16-byte aligned");
-  return check_hip(launch_fill_zero(workspace, workspace_bytes, (hipStream_t)stream), "mes_workspace_init");
-}
-
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream) {
   const char* who = "mes_delta_linear";

@@ -1,9 +1,8 @@
 // The serving hot path (Eq. 4, batched across experts):
 //   y[t] = x[t] W^T + step_e .* (x_ns[t] (U_e - z)^T) + x_s[t] D_e^T
-// for groups of up to 64 tokens.  Per group: one small preparation launch, the main streaming launch
-// and, only when the columns had to be split over workgroups, a small reduction launch.  (Letting the last
-// workgroup of a row group do that reduction inside the main kernel was measured and is slower: the device-wide
-// hand-over costs more than the extra launch.)
+// for groups of up to 64 tokens.  Per group: one small preparation launch, the main streaming launch and, only when
+// the columns had to be split over workgroups, a small reduction launch.  (Letting the last workgroup of a row group do that reduction inside the
+// main kernel was measured and is slower: the device-wide hand-over costs more than the extra launch.)
 //
 // Main kernel.  A workgroup of eight wavefronts (two per SIMD: while one waits for memory or for the
 // matrix core the other issues) owns 128 output channels, one 16-row tile per wavefront, and a range of
@@ -58,6 +57,8 @@ constexpr int kStageLds = kStageBlocks * 1024;  // LDS bytes of one stage
 constexpr int kMaxSlots = 16;                   // experts with tokens in one token group (the host cuts groups accordingly)
 constexpr int kMaxVisits = kMaxSlots + 3;       // (expert, 16-token tile) pairs in one group
 
+constexpr int kMaxSplits = 32;                  // workgroups that may share one row group's columns
+
 constexpr int kMaxLinears = MES_MAX_FUSED;    // linear layers one launch serves (they read the same activations)
 
 // Per linear layer: where its weights, outputs and its share of the workspace are.  Per-expert arrays are indexed by slot.
@@ -65,7 +66,7 @@ struct PerLinear {
   const char* w_base;
   uint16_t* y;
   u32x4* xs;        // workspace: salient activations per visit, fp16, scaled per token  [visit][k_pad/32][64 lanes]
-  float* corr;      // workspace: per-token  z * (sum_all x - sum_salient x)  [64]
+  float* sal_sum;   // workspace: per token, the sum of its activations at its expert's salient columns  [64]
   float* sal_scale; // workspace: per-token power of two the salient activations were divided by  [64]
   const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
@@ -78,7 +79,8 @@ struct PerLinear {
 // Kernel arguments.
 struct LinearParams {
   const uint16_t* x;
-  char* xt;         // workspace: one stage per chunk (see k_prepare), shared by the linears
+  char* xt;         // workspace: one stage per chunk (see prepare_item), shared by the linears
+  float* rowsum;    // workspace: [chunk][64 tokens] sum of the token's activations over the chunk's columns
   f32x4* partial;   // workspace: [row group][nsplit][4 tiles][threads of a workgroup] partial result tiles (split columns only)
   PerLinear lin[kMaxLinears];
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
@@ -86,6 +88,9 @@ struct LinearParams {
   int vis_info[kMaxVisits + 1];           // visits (slot, tile) in tile-major order: slot | tile << 8
   int tile_first[4], tile_last[4];        // slots that own tokens of 16-token tile tt: tile_first[tt] .. tile_last[tt]
   int d_in, n_linears, n_chunks, n_sb, k, T, t0, n_act, n_vis, nsplit, bits;
+  int16_t c_split[kMaxSplits + 1];        // workgroup sp of a row group covers the chunks c_split[sp] .. c_split[sp + 1]
+  int tiles;                              // 16-token tiles of the group that hold tokens
+  int n_stage_items, n_items;             // preparation items: tiles * n_chunks stage items, then n_linears * n_vis gathers
   float z;
 };
 
@@ -206,23 +211,23 @@ __device__ __forceinline__ uint32_t to_e4m3_rtz(float v, float& back) {
   return byte | (sign << 7);
 }
 
-// Block roles by blockIdx.x: [0, 4 n_chunks) build one token tile of one chunk's stage; then per linear n_vis
-// blocks that gather one visit's salient activations and 64 blocks, one per token, for the per-token
-// correction.  256 threads.
+// The preparation launch: one item per block of 256 threads.  Items [0, n_stage_items) build one token tile of one
+// chunk's stage (item = chunk * tiles + tile) and that tile's per-token sums over the chunk's columns; the items after
+// them gather, per linear and visit, the visit's salient activations.
 //
-// Stage of chunk c (what the main kernel copies to LDS), columns counted from 128 c, lane = 16 g + n:
+// Stage of chunk c (what the main loop copies to LDS), columns counted from 128 c, lane = 16 g + n:
 //   bytes [0, 16384)      bf16, [kb][tt][lane][8]: x[16 tt + n][32 kb + 8 g + 0..7]
 //   bytes [16384, 32768)  fp8,  [tt][piece][half][lane][16]: piece (0 = hi, 1 = lo) of
 //                         x[16 tt + n][64 half + 16 g + 0..15] * 2^-s   (the B operand's own column order)
 //   bytes [32768, 33024)  int32 [64]: 128 + s of token 16 tt + n, i.e. the scale byte 2^(s+1) (the extra
 //                         factor two undoes the fp4 codes' u / 2)
 __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
-  const int tid = threadIdx.x;
-  int b = blockIdx.x;
-  if (b < 4 * p.n_chunks) {
+  __shared__ uint32_t smax[16];
+  __shared__ float ssum[64];
+  const int tid = threadIdx.x, item = blockIdx.x;
+  if (item < p.n_stage_items) {
     // (chunk c, token tile tt): thread = (token n of the tile, 8 columns `part` of the chunk's 128)
-    const int c = b >> 2, tt = b & 3;
-    if (p.t0 + 16 * tt >= p.T) return;   // a tile past the last token: the main kernel never reads it
+    const int c = item / p.tiles, tt = item - c * p.tiles;
     char* stage = p.xt + (size_t)c * kStageBytes;
     const int n = tid >> 4, part = tid & 15, q = part >> 2, i = part & 3;
     const int t = p.t0 + 16 * tt + n, col = kChunk * c + 8 * part;
@@ -239,8 +244,13 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     float amax = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(xv[e]));
+    // the token's sum over this chunk (what the zero point is multiplied with), in a fixed order
+    float rs = ((xv[0] + xv[1]) + (xv[2] + xv[3])) + ((xv[4] + xv[5]) + (xv[6] + xv[7]));
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));   // the token's 16 threads
+    for (int off = 1; off < 16; off <<= 1) {   // the token's 16 threads
+      amax = fmaxf(amax, __shfl_xor(amax, off));
+      rs += __shfl_xor(rs, off);
+    }
     // s = exponent(amax) - 7 puts the largest scaled value in [128, 256); clamped so that 128 + s is a
     // valid scale byte.  Non-finite activations give non-finite outputs either way.
     int s = (int)((__float_as_uint(amax) >> 23) & 0xffu) - 127 - 7;
@@ -262,46 +272,48 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     char* dst = stage + kStageFp8 + ((tt * 2 + 0) * 2 + (q >> 1)) * 1024 + lane * 16 + 8 * (i & 1);
     *reinterpret_cast<u32x2*>(dst) = u32x2{hw[0], hw[1]};
     *reinterpret_cast<u32x2*>(dst + 2048) = u32x2{lw[0], lw[1]};
-    if (part == 0) *reinterpret_cast<int*>(stage + kStageScale + (16 * tt + n) * 4) = 128 + s;
+    if (part == 0) {
+      *reinterpret_cast<int*>(stage + kStageScale + (16 * tt + n) * 4) = 128 + s;
+      p.rowsum[c * kTokGroup + 16 * tt + n] = rs;
+    }
     return;
   }
-  b -= 4 * p.n_chunks;
-  const int per_linear = p.n_vis + kTokGroup;
-  const int li = b / per_linear, role = b - li * per_linear;
+  // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
+  // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
+  // within 2^-29 of that largest one, and no value overflows.  The main loop multiplies back.
+  constexpr bool gather_role = true;
+  const int gi = item - p.n_stage_items;
+  const int li = gi / p.n_vis, v = gi - li * p.n_vis;
   const PerLinear& L = p.lin[li];
-  if (role < p.n_vis) {
-    // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
-    // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
-    // within 2^-29 of that largest one, and no value overflows.  The main kernel multiplies back.
-    const int v = role;
-    const int a = p.vis_info[v] & 0xff, tt = p.vis_info[v] >> 8;
-    const int32_t* si = L.sidx[a];
-    __shared__ uint32_t smax[16];
-    if (tid < 16) smax[tid] = 0;
-    __syncthreads();
-    const int lane = tid & 63, n = lane & 15, g = lane >> 4;
-    const int tl = 16 * tt + n;
-    const bool inm = tl >= p.lo[a] && tl < p.hi[a];
-    const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
-    // Item i = (32-column block sb = i / 64, lane = i % 64) is one B-operand register set: eight gathered
-    // activations.  Up to kItems items per thread are gathered once and kept in registers across the
-    // per-token maximum (k <= 512); beyond that the values are gathered a second time.
-    constexpr int kItems = 4;
-    const int n_items = p.n_sb * 64;
-    const bool in_regs = n_items <= 256 * kItems;
-    uint32_t raw[kItems][4];   // two bf16 per word, as gathered
-    auto gather = [&](int i, uint32_t (&w)[4]) {
-      const int sb = i >> 6, gg = (i & 63) >> 4;
+  const int a = p.vis_info[v] & 0xff, tt = p.vis_info[v] >> 8;
+  const int32_t* si = L.sidx[a];
+  if (tid < 16) smax[tid] = 0;
+  __syncthreads();
+  const int lane = tid & 63, n = lane & 15;
+  const int tl = 16 * tt + n;
+  const bool inm = tl >= p.lo[a] && tl < p.hi[a];
+  const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
+  // Item i = (32-column block sb = i / 64, lane = i % 64) is one B-operand register set: eight gathered
+  // activations.  Up to kItems items per thread are gathered once and kept in registers across the
+  // per-token maximum (k <= 512); beyond that the values are gathered a second time.
+  constexpr int kItems = 4;
+  const int n_items = p.n_sb * 64;
+  const bool in_regs = n_items <= 256 * kItems;
+  uint32_t raw[kItems][4];   // two bf16 per word, as gathered
+  auto gather = [&](int i, uint32_t (&w)[4]) {
+    const int sb = i >> 6, gg = (i & 63) >> 4;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r0 = 32 * sb + 8 * gg + 2 * q;   // indices are clamped so that a corrupt list can never address outside the row
-        uint32_t v0 = 0, v1 = 0;
-        if (inm && r0 < p.k) v0 = xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))];
-        if (inm && r0 + 1 < p.k) v1 = xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))];
-        w[q] = v0 | (v1 << 16);
-      }
-    };
-    uint32_t mymax = 0;
+    for (int q = 0; q < 4; ++q) {
+      const int r0 = 32 * sb + 8 * gg + 2 * q;   // indices are clamped so that a corrupt list can never address outside the row
+      uint32_t v0 = 0, v1 = 0;
+      if (inm && r0 < p.k) v0 = xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))];
+      if (inm && r0 + 1 < p.k) v1 = xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))];
+      w[q] = v0 | (v1 << 16);
+    }
+  };
+  uint32_t mymax = 0;
+  float mysum = 0.0f;        // this thread's part of the token's sum over its salient columns
+  if (gather_role) {
     if (in_regs) {
 #pragma unroll
       for (int j = 0; j < kItems; ++j) {
@@ -311,20 +323,35 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
         if (i < n_items) {
           gather(i, raw[j]);
 #pragma unroll
-          for (int q = 0; q < 4; ++q) mymax = max(mymax, max(raw[j][q] & 0x7fffu, (raw[j][q] >> 16) & 0x7fffu));
+          for (int q = 0; q < 4; ++q) {
+            mymax = max(mymax, max(raw[j][q] & 0x7fffu, (raw[j][q] >> 16) & 0x7fffu));
+            mysum += bf16_to_f32((uint16_t)(raw[j][q] & 0xffffu)) + bf16_to_f32((uint16_t)(raw[j][q] >> 16));
+          }
         }
       }
     } else if (inm) {
-      for (int r = tid >> 4; r < p.k; r += 16)
-        mymax = max(mymax, (uint32_t)(xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))] & 0x7fffu));
+      for (int r = tid >> 4; r < p.k; r += 16) {
+        const uint16_t xv = xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))];
+        mymax = max(mymax, (uint32_t)(xv & 0x7fffu));
+        mysum += bf16_to_f32(xv);
+      }
     }
     if (mymax) atomicMax(&smax[tid & 15], mymax);   // (tid & 15) == n: the same token
-    __syncthreads();
+  }
+  // the token's sum: its lanes of this wavefront (n, n + 16, n + 32, n + 48), then the four wavefronts in order
+  mysum += __shfl_xor(mysum, 16);
+  mysum += __shfl_xor(mysum, 32);
+  if (lane < 16) ssum[(tid >> 6) * 16 + lane] = mysum;
+  __syncthreads();
+  if (gather_role) {
     int e = (int)(smax[n] >> 7) - 127 - 14;          // bf16 exponent field of the largest magnitude
     if (smax[n] == 0) e = 0;
     e = e < -110 ? -110 : (e > 110 ? 110 : e);
     const float inv = __uint_as_float((uint32_t)(127 - e) << 23);
-    if (inm && tid < 16) L.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
+    if (inm && tid < 16) {
+      L.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
+      L.sal_sum[tl] = ((ssum[n] + ssum[16 + n]) + ssum[32 + n]) + ssum[48 + n];
+    }
     auto convert_store = [&](int i, const uint32_t (&w)[4]) {
       u32x4 o;
 #pragma unroll
@@ -345,38 +372,7 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
         convert_store(i, w);
       }
     }
-    return;
   }
-  // per-token correction  z (sum_i x_i - sum_{salient} x_i)
-  const int tl = role - p.n_vis;
-  const int t = p.t0 + tl;
-  __shared__ double red[4];
-  double acc = 0.0;
-  if (t < p.T) {
-    const uint16_t* xrow = p.x + (size_t)t * p.d_in;
-    // the salient indices first: the gather below waits for them, the row sum does not
-    const int a = p.tok_slot[tl];
-    const int32_t* si = a != 0xff ? L.sidx[a] : nullptr;
-    int idx0 = -1;
-    if (si != nullptr && tid < p.k) idx0 = (int)min((uint32_t)si[tid], (uint32_t)(p.d_in - 1));
-    for (int c8 = tid; c8 < p.d_in / 8; c8 += 256) {
-      const u32x4 v = *reinterpret_cast<const u32x4*>(xrow + 8 * c8);
-      float part = 0.0f;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) part += bf16_to_f32((uint16_t)(v[q] & 0xffffu)) + bf16_to_f32((uint16_t)(v[q] >> 16));
-      acc += (double)part;
-    }
-    if (idx0 >= 0) acc -= (double)bf16_to_f32(xrow[idx0]);
-    if (si != nullptr)
-      for (int r = tid + 256; r < p.k; r += 256)
-        acc -= (double)bf16_to_f32(xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))]);
-  }
-  // sum over the 256 threads: inside each wavefront by lane exchange, then the four wavefront sums
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
-  if ((tid & 63) == 0) red[tid >> 6] = acc;
-  __syncthreads();
-  if (tid == 0) L.corr[tl] = (float)((double)p.z * (((red[0] + red[1]) + red[2]) + red[3]));
 }
 
 // ---- main kernel ------------------------------------------------------------------------------------
@@ -391,8 +387,18 @@ __device__ __forceinline__ f32x4 mfma_f16(u32x4 a, u32x4 b, f32x4 c) {
 
 // Loads are written as (wave-uniform pointer) + (32-bit unsigned lane offset): the pointer then lives in
 // scalar registers and one vector register per lane serves every stream.
+// The pointers are declared to be device (global) memory: one that has been through keep() has lost the
+// compiler's knowledge of that, and a generic load would also count as an LDS access.
+typedef __attribute__((address_space(1))) const char global_char;
+__device__ __forceinline__ global_char* gptr(const void* q) { return reinterpret_cast<global_char*>(reinterpret_cast<uintptr_t>(q)); }
 __device__ __forceinline__ u32x4 ld128(const void* uniform_ptr, uint32_t lane_off) {
-  return *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(uniform_ptr) + lane_off);
+  return *reinterpret_cast<__attribute__((address_space(1))) const u32x4*>(gptr(uniform_ptr) + lane_off);
+}
+__device__ __forceinline__ int ld32i(const void* uniform_ptr, uint32_t lane_off) {
+  return *reinterpret_cast<__attribute__((address_space(1))) const int*>(gptr(uniform_ptr) + lane_off);
+}
+__device__ __forceinline__ float ld32f(const void* uniform_ptr, uint32_t lane_off) {
+  return *reinterpret_cast<__attribute__((address_space(1))) const float*>(gptr(uniform_ptr) + lane_off);
 }
 
 __device__ __forceinline__ u32x4 lds128(const char* stage, int off) { return *reinterpret_cast<const u32x4*>(stage + off); }
@@ -433,6 +439,21 @@ __device__ __forceinline__ void stage_barrier() {
   asm volatile("s_barrier" ::: "memory");
 }
 
+// A value read from the kernel's argument block is kept in a register from here on.  Left alone the compiler treats
+// such a value as free to fetch again (it is constant memory) wherever scalar registers run short, i.e. all over
+// the streaming loop; every such fetch is a scalar memory load, and while one is in flight every wait for an LDS
+// read of the wavefront has to be a wait for everything, which takes the pipelining out of the operand reads.
+template <class V>
+__device__ __forceinline__ V keep(V v) {
+  asm volatile("" : "+s"(v));
+  return v;
+}
+
+// 16 bytes from a device address held in a lane's registers (a global load, not a generic one: a generic load
+// would also count as an LDS access and make every wait for an operand read wait for memory as well).
+typedef __attribute__((address_space(1))) const u32x4 global_u32x4;
+__device__ __forceinline__ u32x4 ld128_at(uint64_t addr) { return *reinterpret_cast<global_u32x4*>(addr); }
+
 // Per-wavefront state of the streaming loop.
 //  - Base weights are double buffered in registers: while chunk c is multiplied out of buffer c % 2, the
 //    4 KiB of chunk c + 1 are in flight into the other buffer.
@@ -440,9 +461,15 @@ __device__ __forceinline__ void stage_barrier() {
 //    at the top of a chunk the buffer that has arrived is parked in the wavefront's private LDS area and
 //    reloaded at once with the chunk after next.  LDS can be indexed at run time, registers cannot: that
 //    is what lets the loop over the experts of a token tile be a plain loop with a run-time trip count.
+//    The words of all slots of a (chunk, row tile) are fetched 1 KiB per load instruction, 16 bytes per lane,
+//    whatever slot they belong to: the lanes carry their own addresses (the slots' buffers are separate
+//    allocations), worked out once per sweep, and the LDS area is the plain concatenation of the slots' blocks.
+//  - Everything the loop needs of the argument block sits in registers or in two small LDS tables (see keep()).
 template <int BITS, int TT, int NA, int NW>
 struct Stream {
   static constexpr int kSlotLds = code_block_bytes(BITS);       // LDS bytes of one parked slot
+  static constexpr int kParkWave = NA * kSlotLds;               // ... of all slots of a sweep
+  static constexpr int NL = (kParkWave + 1023) / 1024;          // loads of 1 KiB that bring them in
 
   const LinearParams& p;
   const PerLinear& L;
@@ -455,31 +482,52 @@ struct Stream {
   __device__ __forceinline__ int pt(int tt) const { return rev ? TT - 1 - tt : tt; }
   char* parkp;                // this wavefront's LDS area: [NA][kSlotLds]
   // A launch holds up to kMaxSlots experts but only NA of them fit the registers and the LDS area at a time:
-  // the chunks are swept once per group of NA slots (`pass`), the first sweep also doing the base product.
+  // the chunks are swept once per group of NA slots, the first sweep also doing the base product.
   // a0 = first slot of the current sweep.
   int a0 = 0;
-  __device__ __forceinline__ const char* codes_of(int a) const { const int s = a0 + a; return L.codes[s < kMaxSlots ? s : kMaxSlots - 1]; }
+  // launch constants (see keep())
+  const char* xt;             // the activation stages
+  const float* rowsum;
+  const char* xs;             // this linear's gathered salient activations
+  const char* base_at;        // this row tile's base block of chunk 0
+  uint32_t base_stride, code_stride;   // bytes from one chunk's block of this row tile to the next chunk's
+  int n_sb, nsplit;
+  int tfirst[TT], tlast[TT];  // the tile's visits among the slots of the current sweep (slot numbers relative to a0)
+  uint64_t code_at[NL];       // per lane: where its 16 bytes of load i are for chunk 0
+  const int* vis_lds;         // LDS copy of the visit table
+  const uint64_t* sal_lds;    // LDS: per slot, this linear's salient tile of that expert
   uint32_t slot_tok[TT];
+  float rs_acc = 0.0f, rs_in[2];   // lane = token: sum of its activations over the chunks done so far / of the current, next chunk
   int scale[2][TT];           // per-token block scales of the current / next chunk
   u32x4 base[2][4];
-  CodeRegs<BITS> code[2][NA];
+  u32x4 code[2][NL];
   f32x4 acc_base[TT], acc_raw[TT];
 
   // Salient fp16 columns ride along with the stream: the (visit, 32-column block) pairs of this workgroup
   // (pairs sp, sp + nsplit, ... of n_vis * n_sb) are dealt kSalPerChunk to a chunk, requested one chunk before
   // they are multiplied.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
   static constexpr int kSalPerChunk = 1;
-  const float2* tok;   // LDS, per token: .x zero-point correction, .y the power of two its salient activations were divided by
+  const float2* tok;   // LDS, per token: .x sum over its salient columns, .y the power of two its salient activations were divided by
   u32x4 sal_x[kSalPerChunk], sal_d[kSalPerChunk];
   int sal_tt[kSalPerChunk];
   int sal_v, sal_sb, sal_left;   // (visit, block) of the next pair to request; pairs not yet requested
   bool nx_more;                  // the request being prepared: is there a pair, its visit entry, its addresses
-  int nx_info;
-  const char *nx_xp, *nx_dp;
+  int nx_info_v;                 // (as read from LDS: the same in every lane)
+  int nx_tt;
+  uint64_t nx_sal_v;
+  uint32_t nx_xoff, nx_doff;
 
   __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_,
-                                    const float2* tok_, int rev_)
-      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), rev(rev_), parkp(park_), tok(tok_) {
+                                    const float2* tok_, const int* vis_lds_, const uint64_t* sal_lds_, int rev_)
+      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), rev(rev_), parkp(park_), vis_lds(vis_lds_), sal_lds(sal_lds_), tok(tok_) {
+    xt = keep(p.xt);
+    rowsum = keep(p.rowsum);
+    xs = keep(reinterpret_cast<const char*>(L.xs));
+    base_at = keep(L.w_base + (size_t)jt * 4096);
+    base_stride = keep((uint32_t)L.n_jt * 4096u);
+    code_stride = keep((uint32_t)L.n_jt * (uint32_t)kSlotLds);
+    n_sb = keep(p.n_sb);
+    nsplit = keep(p.nsplit);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
       slot_tok[tt] = p.tok_slot[16 * pt(tt) + n];
@@ -488,37 +536,69 @@ struct Stream {
     }
   }
 
+  // The slots a0_ .. a0_ + NA - 1 are the ones multiplied from now on.
+  __device__ __forceinline__ void begin_sweep(int a0_) {
+    a0 = a0_;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+      // a tile with no visit among these slots runs slot 0 of the sweep once with every token's scale 0, like an
+      // empty tile: no branch around the visit loop, no second copy of the accumulator
+      int first = p.tile_first[pt(tt)] - a0, last = p.tile_last[pt(tt)] - a0;
+      first = first < 0 ? 0 : first;
+      last = last > NA - 1 ? NA - 1 : last;
+      if (first > last) first = last = 0;
+      tfirst[tt] = keep(first);
+      tlast[tt] = keep(last);
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int byte = i * 1024 + lane * 16;
+      int s = byte / kSlotLds;
+      const int o = byte - s * kSlotLds;
+      s = s < NA ? s : NA - 1;                        // past the last slot (3-bit planes: 7.5 KiB): re-read, never parked
+      s = a0 + s < kMaxSlots ? a0 + s : kMaxSlots - 1;
+      code_at[i] = reinterpret_cast<uint64_t>(L.codes[s]) + (uint32_t)o + (uint64_t)jt * kSlotLds;
+    }
+  }
+
   __device__ __forceinline__ void sal_begin(int sp) {
-    const int n_pairs = p.n_vis * p.n_sb;
-    sal_left = n_pairs > sp ? (n_pairs - sp + p.nsplit - 1) / p.nsplit : 0;
+    const int n_pairs = p.n_vis * n_sb;
+    sal_left = n_pairs > sp ? (n_pairs - sp + nsplit - 1) / nsplit : 0;
     sal_v = 0;
     sal_sb = sp;
-    while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
+    while (sal_left > 0 && sal_sb >= n_sb) { sal_sb -= n_sb; ++sal_v; }
   }
 
   // A request is made in three steps spread over a chunk, because its addresses sit behind two dependent
-  // look-ups in the argument tables (visit -> slot -> that expert's salient tile) and a wavefront that
-  // issues in order would otherwise sit out both round trips:  look up the visit;  later form the addresses
-  // and move on to the next pair;  later still issue the loads.
+  // look-ups (visit -> slot -> that expert's salient tile; both tables are in LDS) and a wavefront that issues
+  // in order would otherwise sit out both:  look up the visit;  later look up the tile and move on to the next
+  // pair;  later still form the addresses and issue the loads.
   __device__ __forceinline__ void sal_lookup() {
     nx_more = sal_left > 0;
-    nx_info = p.vis_info[nx_more ? sal_v : 0];
+    nx_info_v = vis_lds[nx_more ? sal_v : 0];
   }
   __device__ __forceinline__ void sal_address() {
-    nx_xp = nx_more ? reinterpret_cast<const char*>(L.xs) + ((size_t)sal_v * p.n_sb + sal_sb) * 1024 : p.xt;
-    nx_dp = nx_more ? L.sal[nx_info & 0xff] + ((size_t)jt * p.n_sb + sal_sb) * 1024 : p.xt;
+    const int info = __builtin_amdgcn_readfirstlane(nx_info_v);
+    nx_tt = nx_more ? info >> 8 : -1;
+    nx_sal_v = sal_lds[info & 0xff];
+    nx_xoff = ((uint32_t)sal_v * (uint32_t)n_sb + (uint32_t)sal_sb) * 1024u;
+    nx_doff = ((uint32_t)jt * (uint32_t)n_sb + (uint32_t)sal_sb) * 1024u;
     if (nx_more) {
       --sal_left;
-      sal_sb += p.nsplit;
-      while (sal_left > 0 && sal_sb >= p.n_sb) { sal_sb -= p.n_sb; ++sal_v; }
+      sal_sb += nsplit;
+      while (sal_left > 0 && sal_sb >= n_sb) { sal_sb -= n_sb; ++sal_v; }
     }
   }
   // Always two loads, so that the number of loads in flight does not depend on the data: once the pairs are
   // used up both read the start of the activation stages and tt_out = -1.
   __device__ __forceinline__ void sal_issue(u32x4& x, u32x4& d, int& tt_out) {
-    tt_out = nx_more ? nx_info >> 8 : -1;
-    x = ld128(nx_xp, (uint32_t)lane * 16u);
-    d = ld128(nx_dp, (uint32_t)lane * 16u);
+    tt_out = nx_tt;
+    const bool more = nx_tt >= 0;
+    // the tile pointer was read from LDS a good while ago and is the same in every lane: into scalar registers with it
+    const uint64_t tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(nx_sal_v >> 32)) << 32) |
+                          (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)nx_sal_v);
+    x = ld128(more ? xs + nx_xoff : xt, (uint32_t)lane * 16u);
+    d = ld128(more ? reinterpret_cast<const char*>(tile) + nx_doff : xt, (uint32_t)lane * 16u);
   }
 
   // The pair's 16 x 16 product goes to the base accumulators of its token tile, times the tokens' scale.  Which
@@ -539,39 +619,35 @@ struct Stream {
 
   template <int BUF>
   __device__ __forceinline__ void load_base(int c) {
-    const char* src = L.w_base + ((size_t)c * L.n_jt + jt) * 4096;
+    const char* src = base_at + (size_t)((uint32_t)c * base_stride);
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
   }
 
   template <int BUF>
   __device__ __forceinline__ void load_scales(int c) {
-    const int* src = reinterpret_cast<const int*>(p.xt + (size_t)c * kStageBytes + kStageScale);
+    const char* src = xt + (size_t)c * kStageBytes + kStageScale;
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = src[16 * pt(tt) + n];
+    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = ld32i(src + 64 * pt(tt), (uint32_t)n * 4u);
   }
 
   template <int BUF>
+  __device__ __forceinline__ void load_rowsum(int c) { rs_in[BUF] = ld32f(rowsum + c * kTokGroup, (uint32_t)lane * 4u); }
+
+  template <int BUF>
   __device__ __forceinline__ void load_code_regs(int c) {
-    const size_t off = ((size_t)c * L.n_jt + jt) * kSlotLds;
+    const uint32_t off = (uint32_t)c * code_stride;
 #pragma unroll
-    for (int a = 0; a < NA; ++a) load_codes<BITS>(codes_of(a) + off, lane, code[BUF][a]);
+    for (int i = 0; i < NL; ++i) code[BUF][i] = ld128_at(code_at[i] + off);
   }
 
   // Register buffer BUF (the chunk that starts now) -> this wavefront's LDS area.
   template <int BUF>
   __device__ __forceinline__ void park() {
 #pragma unroll
-    for (int a = 0; a < NA; ++a) {
-      char* dst = parkp + a * kSlotLds;
-      const CodeRegs<BITS>& r = code[BUF][a];
-      if constexpr (BITS == 1) {
-        *reinterpret_cast<uint32_t*>(dst + lane * 4) = r.lo[0];
-      } else {
-        *reinterpret_cast<u32x2*>(dst + lane * 8) = u32x2{r.lo[0], r.lo[1]};
-        if constexpr (BITS == 3) *reinterpret_cast<uint32_t*>(dst + 512 + lane * 4) = r.hi[0];
-        if constexpr (BITS == 4) *reinterpret_cast<u32x2*>(dst + 512 + lane * 8) = u32x2{r.hi[0], r.hi[1]};
-      }
+    for (int i = 0; i < NL; ++i) {
+      if (NL * 1024 == kParkWave || i * 1024 + lane * 16 < kParkWave)
+        *reinterpret_cast<u32x4*>(parkp + i * 1024 + lane * 16) = code[BUF][i];
     }
   }
 
@@ -579,17 +655,19 @@ struct Stream {
   // that was just parked, base weights and scales of chunk cn (one ahead) into the other base buffer.
   template <int BUF, bool NOBASE>
   __device__ __forceinline__ void request_share(int tt, int cn, int c2) {
-    const size_t off = ((size_t)c2 * L.n_jt + jt) * kSlotLds;
+    const uint32_t off = (uint32_t)c2 * code_stride;
 #pragma unroll
-    for (int a = 0; a < NA; ++a)
-      if (a * TT / NA == tt) load_codes<BITS>(codes_of(a) + off, lane, code[BUF][a]);
+    for (int i = 0; i < NL; ++i)
+      if (i * TT / NL == tt) code[BUF][i] = ld128_at(code_at[i] + off);
     if constexpr (!NOBASE) {
-      const char* src = L.w_base + ((size_t)cn * L.n_jt + jt) * 4096;
+      const char* src = base_at + (size_t)((uint32_t)cn * base_stride);
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
         if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
     }
-    scale[BUF ^ 1][tt] = *reinterpret_cast<const int*>(p.xt + (size_t)cn * kStageBytes + kStageScale + 64 * pt(tt) + (uint32_t)n * 4u);
+    scale[BUF ^ 1][tt] = ld32i(xt + (size_t)cn * kStageBytes + kStageScale + 64 * pt(tt), (uint32_t)n * 4u);
+    if constexpr (!NOBASE)
+      if (tt == 0) rs_in[BUF ^ 1] = ld32f(rowsum + cn * kTokGroup, (uint32_t)lane * 4u);
   }
 
   __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
@@ -599,14 +677,15 @@ struct Stream {
   }
 
   // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
-  template <bool NOBASE> static constexpr int younger() { return NA * (BITS >= 3 ? 2 : 1) + (NOBASE ? 0 : 4) + TT + 2 * kSalPerChunk; }
+  template <bool NOBASE> static constexpr int younger() { return NL + (NOBASE ? 0 : 5) + TT + 2 * kSalPerChunk; }
 
   // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
   // NOBASE: a sweep after the first -- the base product is done, only the slots of this sweep are multiplied.
   template <int BUF, bool NOBASE>
   __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave) {
-    stage_copy<NW>(p.xt + (size_t)cn * kStageBytes, nxt, wave, lane);
+    stage_copy<NW>(xt + (size_t)cn * kStageBytes, nxt, wave, lane);
     sal_lookup();
+    if constexpr (!NOBASE) rs_acc += rs_in[BUF];   // this chunk's share of the tokens' sums (requested a chunk ago)
     // Order inside a tile: the low-bit visits first (operands bhi / blo, read from LDS during the previous
     // tile's base product), then the base product (operands xb, read while the visits ran).  Every LDS read is
     // thereby issued a good stretch of arithmetic before its data are needed.
@@ -617,21 +696,14 @@ struct Stream {
       // pipeline fed without ever asking it to take a whole chunk's loads at once (which blocks the
       // wavefront, and with it the arithmetic it could be doing, until the pipeline has room)
       request_share<BUF, NOBASE>(tt, cn, c2);
-      // the tile's visits among the slots of this sweep (slot numbers relative to a0); a tile with none runs
-      // slot 0 of the sweep once with every token's scale 0, like an empty tile
-      int first = p.tile_first[pt(tt)] - a0, last = p.tile_last[pt(tt)] - a0;
-      first = first < 0 ? 0 : first;
-      last = last > NA - 1 ? NA - 1 : last;
-      if (first > last) first = last = 0;
-      CodeRegs<BITS> cr = parked(first);
+      const int last = tlast[tt];
+      int a = tfirst[tt];
+      CodeRegs<BITS> cr = parked(a);
       u32x4 xb[4];
       if constexpr (!NOBASE) {
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + pt(tt)) * 1024 + lane * 16);
       }
-      // every tile of the launch has at least one visit (the host gives an empty tile slot 0, whose tokens
-      // are nobody's: scale 0), so there is no branch around the loop and no second copy of the accumulator
-      int a = first;
       do {
         const int sc = slot_tok[tt] == (uint32_t)(a + a0) ? scale[BUF][tt] : 0;
         const u32x4 d = dequant_lo<BITS>(cr);
@@ -672,26 +744,28 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   int jt = (rg - L.rg_begin) * NW + wave;
   const bool live = jt < L.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
   jt = live ? jt : L.n_jt - 1;
-  const int c_begin = (int)((long)sp * p.n_chunks / p.nsplit);
-  const int c_end = (int)((long)(sp + 1) * p.n_chunks / p.nsplit);
+  const int c_begin = p.c_split[sp], c_end = p.c_split[sp + 1];
 
   // One LDS block carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
   // offset field of the LDS instructions, so one lane-offset register serves every operand read.
   //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | parked code words, one private area per wavefront |
-  //   per wavefront and slot the 16 steps | per token (correction, salient scale)
+  //   per wavefront and slot the 16 steps | per token (salient sum, salient scale) | visit table | salient tile table
   constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
   constexpr int kLaunchSlots = NA == 4 ? 4 : kMaxSlots;   // experts of one launch; NA of them per sweep
   constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
-  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + 256];
+  constexpr int kVisBytes = (kMaxVisits + 1 + 3) / 4 * 16;
+  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes + kMaxSlots * 8 + 256];
   char* const stage0 = lds;
   char* const stage1 = lds + kStageLds;
   char* const park_all = lds + 2 * kStageLds;
   float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + 2 * kStageLds + kParkBytes);
   float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
-  char* const warm_lds = lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8;   // 256 bytes nobody reads
+  int* const vis_lds = reinterpret_cast<int*>(lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8);
+  uint64_t* const sal_lds = reinterpret_cast<uint64_t*>(lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes);
+  char* const warm_lds = lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes + kMaxSlots * 8;   // 256 bytes nobody reads
 
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds, vis_lds, sal_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -703,40 +777,42 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   const int len = c_end - c_begin;
   const int rot = ((rg & 7) * len) >> 3;
   auto chunk_at = [&](int i) { i = i < len ? i : len - 1; int r = i + rot; r = r >= len ? r - len : r; return c_begin + r; };
-  // Address translation warm-up.  The first loads of a workgroup go to as many pages as there are experts, and
-  // a wavefront issues in order: left alone, each would sit out one translation miss after the other (about
-  // 0.1 us each, 3 us for 32 code-word loads).  Instead the wavefronts split the (slot, chunk) combinations among
-  // themselves and touch each page once with a 4-byte LDS-DMA load (no destination register to keep track
-  // of), all in parallel; the real loads below then find their translations cached.
+  ws.begin_sweep(0);
+  // Address translation warm-up.  The first loads of a workgroup go to as many pages as there are experts; one
+  // 4-byte LDS-DMA load (no destination register to keep track of) touches the first two chunks' pages of every
+  // slot at once, lanes 0 .. 15 those of the first chunk and lanes 16 .. 31 those of the second.
   {
-    constexpr int kCombos = 2 * NA, kPer = (kCombos + NW - 1) / NW;
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-      const int combo = (wave * kPer + i) % kCombos;
-      const int a = combo >> 1;
-      const char* g = L.codes[a < p.n_act ? a : 0] + ((size_t)chunk_at(combo & 1) * L.n_jt + jt) * code_block_bytes(BITS);
-      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-                   : : "v"((uint32_t)lane * 4u), "s"(g), "s"((uint32_t)(uintptr_t)warm_lds) : "memory", "m0");
-    }
+    const int a = lane & 15;
+    const uint64_t g = reinterpret_cast<uint64_t>(L.codes[a < p.n_act ? a : 0]) +
+                       ((uint64_t)chunk_at((lane >> 4) & 1) * L.n_jt + jt) * code_block_bytes(BITS);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 : : "v"(g), "s"((uint32_t)(uintptr_t)warm_lds) : "memory", "m0");
   }
-  // first chunks' activations and weights: requested now, needed after the salient product below
-  stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
+  // first chunks' weights and activations: requested now
+  stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
   ws.template load_base<0>(chunk_at(0));
   ws.template load_scales<0>(chunk_at(0));
+  ws.template load_rowsum<0>(chunk_at(0));
   ws.template load_code_regs<0>(chunk_at(0));
   ws.template load_code_regs<1>(chunk_at(1));
-  // What the epilogue needs -- every slot's step for this wavefront's 16 output channels, and per token the
-  // zero-point correction and the salient scale -- is fetched now and kept in LDS until then: in registers
-  // it would be live across the whole stream.  (The correction belongs to the whole column range: only the
-  // first split applies it.)
+  // What the epilogue needs -- every slot's step for this wavefront's 16 output channels, and per token the sum
+  // over its salient columns (subtracted by the first split only: it belongs to the whole column range) and the
+  // salient scale -- is fetched now and kept in LDS until then: in registers it would be live across the whole
+  // stream.  Likewise the two tables of the salient requests.
   const int st_a = lane >> 2, st_j = 16 * jt + 4 * (lane & 3);
   f32x4 st_v = {0, 0, 0, 0};
   if (st_a < kLaunchSlots && st_a < p.n_act && st_j < L.d_out) st_v = *reinterpret_cast<const f32x4*>(L.step[st_a] + st_j);
   float2 tok_v = {0.0f, 0.0f};
-  if (tid < kTokGroup) tok_v = float2{sp == 0 ? L.corr[tid] : 0.0f, L.sal_scale[tid]};
+  if (tid < kTokGroup && p.n_vis > 0) tok_v = float2{sp == 0 ? L.sal_sum[tid] : 0.0f, L.sal_scale[tid]};
+  int vis_v = 0;
+  uint64_t sal_v = 0;
+  if (tid <= kMaxVisits) vis_v = p.vis_info[tid];
+  if (tid < kMaxSlots) sal_v = reinterpret_cast<uint64_t>(L.sal[tid]);
   ws.sal_begin(sp);
   if (st_a < kLaunchSlots) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
   if (tid < kTokGroup) tok_lds[tid] = tok_v;
+  if (tid <= kMaxVisits) vis_lds[tid] = vis_v;
+  if (tid < kMaxSlots) sal_lds[tid] = sal_v;
 
   ws.template park<0>();
   stage_barrier<0>();
@@ -761,8 +837,8 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   // slots' code words, no base weights.  The last barrier of the sweep before has every wavefront done with
   // both stages.
   for (int sweep = 1; sweep < n_sweeps; ++sweep) {
-    ws.a0 = sweep * NA;
-    stage_copy<NW>(p.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
+    ws.begin_sweep(sweep * NA);
+    stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
     ws.template load_scales<0>(chunk_at(0));
     ws.template load_code_regs<0>(chunk_at(0));
     ws.template load_code_regs<1>(chunk_at(1));
@@ -784,10 +860,11 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   for (int tt = 0; tt < TT; ++tt) {
     f32x4 stepv = {0, 0, 0, 0};
     if (slot_tok[tt] != 0xffu) stepv = *reinterpret_cast<const f32x4*>(&step_lds[wave][slot_tok[tt]][4 * g]);
-    const float2 tk = tok_lds[16 * ws.pt(tt) + n];
+    // zero point: z (sum over this workgroup's columns - sum over the token's salient columns)
+    const float corr = p.z * (__shfl(ws.rs_acc, 16 * ws.pt(tt) + n) - tok_lds[16 * ws.pt(tt) + n].x);
 #pragma unroll
     for (int v = 0; v < 4; ++v)
-      o[tt][v] = acc_base[tt][v] + stepv[v] * (acc_raw[tt][v] - tk.x);
+      o[tt][v] = acc_base[tt][v] + stepv[v] * (acc_raw[tt][v] - corr);
   }
 
   if (p.nsplit > 1) {
@@ -797,17 +874,16 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
     f32x4* part = p.partial + ((size_t)rg * p.nsplit + sp) * (4 * NT);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) part[ws.pt(tt) * NT + tid] = o[tt];
-    return;
-  }
-  if (!live) return;
+  } else if (live) {
 #pragma unroll
-  for (int tt = 0; tt < TT; ++tt) {
-    const int t = p.t0 + 16 * ws.pt(tt) + n, j = 16 * jt + 4 * g;
-    if (t < p.T && j < L.d_out) {
-      uint2 pk;
-      pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
-      pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
-      *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
+    for (int tt = 0; tt < TT; ++tt) {
+      const int t = p.t0 + 16 * ws.pt(tt) + n, j = 16 * jt + 4 * g;
+      if (t < p.T && j < L.d_out) {
+        uint2 pk;
+        pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
+        pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
+        *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
+      }
     }
   }
 }
@@ -835,7 +911,7 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p)
 
 // Active experts one launch handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
 // 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
-constexpr int max_pass_slots(int bits) { return bits == 4 ? 8 : bits == 3 ? 10 : 16; }
+constexpr int max_pass_slots(int bits) { return bits >= 3 ? 8 : 16; }
 
 // Wavefronts per workgroup (each owns 16 output channels): 8 fill a compute unit's four SIMDs two deep; 7 or 6
 // are chosen when that makes the number of workgroups fit the 256 compute units better.
@@ -859,7 +935,7 @@ Plan plan_for(int d_in, const int* d_out, int n_linears) {
   for (int nw = kMaxWaves; nw >= 6; --nw) {
     int rgs = 0;
     for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], nw);
-    for (int ns = 1; ns <= 32 && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
+    for (int ns = 1; ns <= kMaxSplits && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
       const long wgs = (long)rgs * ns;
       const long rounds = (wgs + 255) / 256;
       const int chunks_wg = (n_chunks + ns - 1) / ns;
@@ -873,7 +949,7 @@ Plan plan_for(int d_in, const int* d_out, int n_linears) {
 }
 
 struct WorkspaceLayout {
-  size_t xt, per_linear[kMaxLinears], partial, total;   // per linear: xs, then corrections and salient scales
+  size_t xt, rowsum, per_linear[kMaxLinears], partial, total;   // per linear: xs, then the tokens' salient sums and scales
   size_t xs_bytes;
 };
 
@@ -885,6 +961,7 @@ WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
   WorkspaceLayout w;
   size_t off = 0;
   w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes;
+  w.rowsum = off;  off += (size_t)(pi / kChunk) * kTokGroup * 4;
   w.xs_bytes = (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
   for (int l = 0; l < kMaxLinears; ++l) {
     w.per_linear[l] = off;
@@ -953,6 +1030,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   LinearParams p;
   p.x = reinterpret_cast<const uint16_t*>(c.x);
   p.xt = ws + wl.xt;
+  p.rowsum = reinterpret_cast<float*>(ws + wl.rowsum);
   p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
   const int pi = ceil_to(d0.d_in, kColPad);
   p.d_in = d0.d_in;
@@ -970,8 +1048,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     L.w_base = reinterpret_cast<const char*>(c.lin[ll].w_base_tiled);
     L.y = reinterpret_cast<uint16_t*>(c.lin[ll].y);
     L.xs = reinterpret_cast<u32x4*>(ws + wl.per_linear[ll]);
-    L.corr = reinterpret_cast<float*>(ws + wl.per_linear[ll] + wl.xs_bytes);
-    L.sal_scale = L.corr + kTokGroup;
+    L.sal_sum = reinterpret_cast<float*>(ws + wl.per_linear[ll] + wl.xs_bytes);
+    L.sal_scale = L.sal_sum + kTokGroup;
     L.d_out = d_outs[ll];
     L.n_jt = ceil_to(d_outs[ll], kRowPad) / 16;
     L.rg_begin = rgs;
@@ -979,6 +1057,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     L.rg_end = rgs;
   }
   p.nsplit = pl.nsplit;
+  for (int sp = 0; sp <= pl.nsplit; ++sp) p.c_split[sp] = (int16_t)((long)sp * p.n_chunks / pl.nsplit);
   const dim3 grid(rgs, pl.nsplit);
   // Token groups: up to 64 consecutive tokens that belong to at most kMaxSlots experts (the kernel sweeps the
   // chunks once per max_pass_slots of them).
@@ -1044,7 +1123,10 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     p.n_act = na;
     p.n_vis = d0.k > 0 ? nv : 0;
     p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
-    k_prepare<<<4 * p.n_chunks + c.n_linears * (p.n_vis + kTokGroup), 256, 0, s>>>(p);
+    p.tiles = (nt + 15) / 16;
+    p.n_stage_items = p.tiles * p.n_chunks;
+    p.n_items = p.n_stage_items + c.n_linears * p.n_vis;
+    k_prepare<<<p.n_items, 256, 0, s>>>(p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (c.ev_start && first_kernel && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;

@@ -142,12 +142,10 @@ def test_delta_linear_multi_argument_errors():
     assert lib.mes_linear_multi_workspace_bytes(64, d2, 4, 64) == 0
 
 
-def test_unpack_and_workspace_init_argument_errors():
+def test_unpack_argument_errors():
     d = _desc()
     assert lib.mes_unpack_delta(ctypes.byref(d), None, None, None) == 1
     assert lib.mes_unpack_delta(None, FAKE, None, None) == 1
-    assert lib.mes_workspace_init(None, 64, None) == 1
-    assert lib.mes_workspace_init(ODD, 64, None) == 6
 
 
 def test_copy_probe_argument_errors():
