@@ -181,6 +181,19 @@ mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, 
 mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
                                   const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream);
 
+/* mes_delta_linear for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * mes_delta_linear, except that the per-call scratch lives in a device-resident static array of
+ * mes_noalloc_scratch_bytes() bytes (64 MiB; every GPU the library runs on holds its own copy until the process
+ * ends) instead of a caller-owned workspace.  The call works on the device that is current when it is made
+ * (`stream` must belong to it), allocates and frees nothing, never synchronises, and returns MES_ERR_WORKSPACE
+ * if a layer of this shape needs more scratch than the array holds (mes_linear_workspace_bytes(d_in, d_out, 1)
+ * > mes_noalloc_scratch_bytes(); every Mistral-7B shape fits).  All calls on one GPU share that GPU's array:
+ * they must be stream-ordered, calls that overlap on one GPU race. */
+size_t mes_noalloc_scratch_bytes(void);
+mes_status mes_delta_linear_noalloc(const void* w_base_tiled, const mes_delta* experts, int n_experts,
+                                    const void* x, int T, const int32_t* seg_offsets, void* y, void* stream);
+
 /* ---- on-demand swapping (Section 4.1, "On-demand swapping": the base model stays on the GPU, the compressed
  * deltas of the experts a batch needs are loaded when they are needed) ----------------------------------------
  * A pool serves ONE linear layer.  It owns nothing but its bookkeeping: the caller gives it a DEVICE arena of

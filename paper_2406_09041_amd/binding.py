@@ -30,7 +30,8 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_delta_linear", "mes_linear_multi_workspace_bytes",
            "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
            "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
-           "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_long_segment_tokens"]
+           "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_noalloc_scratch_bytes",
+           "mes_delta_linear_noalloc", "mes_long_segment_tokens"]
 
 
 class MesError(RuntimeError):
@@ -86,6 +87,11 @@ def _load() -> ctypes.CDLL:
                                      ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
     lib.mes_long_segment_tokens.restype = c_int
     lib.mes_long_segment_tokens.argtypes = []
+    lib.mes_noalloc_scratch_bytes.restype = c_sz
+    lib.mes_noalloc_scratch_bytes.argtypes = []
+    lib.mes_delta_linear_noalloc.restype = c_int
+    lib.mes_delta_linear_noalloc.argtypes = [vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
+                                             ctypes.POINTER(ctypes.c_int32), vp, vp]
     lib.mes_linear_multi_workspace_bytes.restype = c_sz
     lib.mes_linear_multi_workspace_bytes.argtypes = [c_int, ctypes.POINTER(ctypes.c_int32), c_int, c_int]
     lib.mes_delta_linear_multi.restype = c_int
@@ -288,6 +294,16 @@ class DeltaLinear:
 
 def mes_delta_linear(w_base_tiled, experts, x, seg_offsets, y=None, workspace=None):
     return DeltaLinear(w_base_tiled, experts, x.shape[0], workspace)(x, seg_offsets, y)
+
+
+def mes_delta_linear_noalloc(w_base_tiled: torch.Tensor, experts: Sequence[PackedDelta], x: torch.Tensor,
+                             seg_offsets: Sequence[int], y: torch.Tensor) -> torch.Tensor:
+    """mes_delta_linear_noalloc: the scratch is the library's device-resident static array; y is the caller's."""
+    E, T = len(experts), x.shape[0]
+    desc = (mes_delta * E)(*[e.descriptor() for e in experts])
+    seg = (ctypes.c_int32 * (E + 1))(*seg_offsets)
+    _check(lib.mes_delta_linear_noalloc(_ptr(w_base_tiled), desc, E, _ptr(x), T, seg, _ptr(y), _stream(x.device)))
+    return y
 
 
 def mes_delta_linear_descriptors(w_base_tiled: torch.Tensor, desc, x: torch.Tensor, seg_offsets: Sequence[int],

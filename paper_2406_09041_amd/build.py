@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmes.so")
-SOURCES = ["mes_api.hip", "mes_pack.hip", "mes_linear.hip", "mes_pool.hip", "mes_prefill.hip", "mes_step.hip"]
+SOURCES = ["mes_api.hip", "mes_pack.hip", "mes_linear.hip", "mes_pool.hip", "mes_prefill.hip", "mes_step.hip", "mes_noalloc.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

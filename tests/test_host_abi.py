@@ -148,6 +148,21 @@ def test_unpack_argument_errors():
     assert lib.mes_unpack_delta(None, FAKE, None, None) == 1
 
 
+def test_noalloc_entry_point_argument_errors():
+    """The allocation-free entry point checks its limit on the host, before any GPU call."""
+    assert lib.mes_noalloc_scratch_bytes() == 64 << 20
+    seg = (ctypes.c_int32 * 2)(0, 4)
+    d = _desc()
+    assert lib.mes_delta_linear_noalloc(FAKE, None, 1, FAKE, 4, seg, FAKE, None) == 1
+    assert lib.mes_delta_linear_noalloc(FAKE, ctypes.byref(d), 0, FAKE, 4, seg, FAKE, None) == 2
+    huge = _desc(d_in=1 << 20, d_out=1 << 20)
+    assert lib.mes_linear_workspace_bytes(1 << 20, 1 << 20, 1) > lib.mes_noalloc_scratch_bytes()
+    assert lib.mes_delta_linear_noalloc(FAKE, ctypes.byref(huge), 1, FAKE, 4, seg, FAKE, None) == 7
+    assert b"static array" in lib.mes_last_error()
+    for d_in, d_out in [(4096, 4096), (4096, 1024), (4096, 14336), (14336, 4096)]:      # every Mistral-7B shape fits
+        assert 0 < lib.mes_linear_workspace_bytes(d_in, d_out, 1) <= lib.mes_noalloc_scratch_bytes()
+
+
 def test_copy_probe_argument_errors():
     lib = B.lib
     assert lib.mes_copy_probe(None, 16, 16, None) == 1
