@@ -17,19 +17,20 @@
 //            00uu is the number u / 2 and 0h00 is 2 h, so the packed codes become the A operand with one
 //            AND (plus one shift for every second register): no conversion, no multiply.  The activations
 //            are split by the preparation kernel into two fp8 pieces, x * 2^-s = hi + lo with s a power of
-//            two per (token, chunk); hi carries the top four significant bits of the bf16 value and lo the
-//            other four, so the two products together are the exact bf16 x code product whenever the value
-//            is within 2^-10 of the largest of its token in the chunk (below that the piece is truncated at
+//            two per (token, chunk); hi is the value rounded to four significant bits and lo the remainder
+//            (four bits at most), so the two products together are the exact bf16 x code product whenever
+//            the value is within 2^-10 of the largest of its token in the chunk (below that lo is rounded at
 //            2^-17 of that largest value).  The instruction's per-lane block scale (a power of two applied
 //            to a token's products) carries 2^(s+1) for tokens of the expert being multiplied and 2^-127
 //            for every other token of the tile -- that is how several experts share a 16-token tile.
-//   salient  v_mfma_f32_16x16x32_f16: the expert's fp16 tile as stored x the activations at its salient
-//            columns, converted bf16 -> fp16 by the preparation kernel after an exact per-token power-of-two
-//            scaling that keeps them inside the fp16 range.
+//   salient  v_mfma_f32_16x16x32_bf16, twice: the activations at the expert's salient columns as gathered (bf16,
+//            nothing converted) x the expert's fp16 values D, each written as the sum of two bf16 numbers
+//            (8 + 8 significant bits hold the 11 of an fp16 value, and then some).
 // Zero point and per-output-channel step are applied after the reduction:
-//   sum over non-salient i of x_i (u_i - z) = sum_all x_i u_i - z (sum_all x_i - sum_salient x_i),
-// (codes stored at salient and padding columns are 0), the bracket being a per-token number the
-// preparation kernel provides.
+//   sum over non-salient i of x_i (u_i - z) = sum_all x_i u_i - z sum_all x_i + z sum_salient x_i
+// (codes stored at salient and padding columns are 0).  The middle term is a per-token number (the preparation
+// leaves per-chunk sums, the loop adds them up); the last one, times the step, is folded into the salient product:
+// its weights are D + z step instead of D.
 //
 // Slots.  The host lists the experts that own tokens of the group ("slots", in expert order; an expert
 // with an empty segment is never touched).  Tokens are sorted by expert, so the slots with tokens in one
@@ -46,14 +47,17 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 typedef int v8i __attribute__((ext_vector_type(8)));
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
 
 constexpr int kChunk = 128;                     // columns per chunk (one fp4 x fp8 MFMA deep)
 constexpr int kStageVec = 2048;                 // 16-byte slots of activations per chunk
-constexpr int kStageBytes = kStageVec * 16 + 256;   // + one block scale per token
+constexpr int kStageBytes = kStageVec * 16 + 1024;  // + a block of per-token numbers (block scales, sums)
 constexpr int kStageFp8 = 16384;                // byte offset of the fp8 pieces inside a stage
 constexpr int kStageScale = 32768;              // byte offset of the scales inside a stage
-constexpr int kStageBlocks = 32;                // 1 KiB blocks the main kernel copies to LDS per chunk (the scales are read from memory)
-constexpr int kStageLds = kStageBlocks * 1024;  // LDS bytes of one stage
+constexpr int kStageSum = 32768 + 256;          // byte offset of the tokens' sums over the chunk's columns
+constexpr int kStageBlocks = 33;                // 1 KiB blocks the main kernel copies to LDS per chunk
+constexpr int kStageLds = 32 * 1024;            // LDS bytes of a stage's operand images; its 33rd block sits apart (see k_delta_linear)
 constexpr int kMaxSlots = 16;                   // experts with tokens in one token group (the host cuts groups accordingly)
 constexpr int kMaxVisits = kMaxSlots + 3;       // (expert, 16-token tile) pairs in one group
 
@@ -65,9 +69,7 @@ constexpr int kMaxLinears = MES_MAX_FUSED;    // linear layers one launch serves
 struct PerLinear {
   const char* w_base;
   uint16_t* y;
-  u32x4* xs;        // workspace: salient activations per visit, fp16, scaled per token  [visit][k_pad/32][64 lanes]
-  float* sal_sum;   // workspace: per token, the sum of its activations at its expert's salient columns  [64]
-  float* sal_scale; // workspace: per-token power of two the salient activations were divided by  [64]
+  u32x4* xs;        // workspace: salient activations per visit, bf16 as gathered  [visit][k_pad/32][64 lanes]
   const char* codes[kMaxSlots];
   const float* step[kMaxSlots];
   const char* sal[kMaxSlots];
@@ -80,7 +82,6 @@ struct PerLinear {
 struct LinearParams {
   const uint16_t* x;
   char* xt;         // workspace: one stage per chunk (see prepare_item), shared by the linears
-  float* rowsum;    // workspace: [chunk][64 tokens] sum of the token's activations over the chunk's columns
   f32x4* partial;   // workspace: [row group][nsplit][4 tiles][threads of a workgroup] partial result tiles (split columns only)
   PerLinear lin[kMaxLinears];
   int16_t lo[kMaxSlots], hi[kMaxSlots];   // tokens [lo, hi) of the group belong to the slot's expert
@@ -194,23 +195,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
 // ---- preparation ------------------------------------------------------------------------------------
-// v (|v| < 256) truncated toward zero onto the E4M3 grid; `back` receives the value of the returned byte.
-__device__ __forceinline__ uint32_t to_e4m3_rtz(float v, float& back) {
-  const uint32_t u = __float_as_uint(v), sign = u >> 31, a = u & 0x7fffffffu;
-  uint32_t byte;
-  float mag;
-  if (a >= 0x3c800000u) {   // |v| >= 2^-6: a normal E4M3 number, three mantissa bits kept
-    byte = (((a >> 23) - 120u) << 3) | ((a >> 20) & 7u);
-    mag = __uint_as_float(a & 0xfff00000u);
-  } else {                  // a multiple of 2^-9 below 2^-6
-    const uint32_t m = (uint32_t)(__uint_as_float(a) * 512.0f);
-    byte = m;
-    mag = (float)m * (1.0f / 512.0f);
-  }
-  back = sign ? -mag : mag;
-  return byte | (sign << 7);
-}
-
 // The preparation launch: one item per block of 256 threads.  Items [0, n_stage_items) build one token tile of one
 // chunk's stage (item = chunk * tiles + tile) and that tile's per-token sums over the chunk's columns; the items after
 // them gather, per linear and visit, the visit's salient activations.
@@ -221,9 +205,9 @@ __device__ __forceinline__ uint32_t to_e4m3_rtz(float v, float& back) {
 //                         x[16 tt + n][64 half + 16 g + 0..15] * 2^-s   (the B operand's own column order)
 //   bytes [32768, 33024)  int32 [64]: 128 + s of token 16 tt + n, i.e. the scale byte 2^(s+1) (the extra
 //                         factor two undoes the fp4 codes' u / 2)
+//   bytes [33024, 33280)  float [64]: sum of the token's activations over the chunk's columns; the rest of the
+//                         33rd KiB is padding
 __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
-  __shared__ uint32_t smax[16];
-  __shared__ float ssum[64];
   const int tid = threadIdx.x, item = blockIdx.x;
   if (item < p.n_stage_items) {
     // (chunk c, token tile tt): thread = (token n of the tile, 8 columns `part` of the chunk's 128)
@@ -257,121 +241,54 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
     if (amax == 0.0f) s = 0;
     s = s < -126 ? -126 : (s > 120 ? 120 : s);
     const float inv = __uint_as_float((uint32_t)(127 - s) << 23);   // 2^-s
-    uint32_t hw[2] = {0, 0}, lw[2] = {0, 0};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float sv = xv[e] * inv;
-      float hv, lv;
-      const uint32_t hb = to_e4m3_rtz(sv, hv);
-      const uint32_t lb = to_e4m3_rtz(sv - hv, lv);
-      hw[e >> 2] |= hb << (8 * (e & 3));
-      lw[e >> 2] |= lb << (8 * (e & 3));
+    // hi = x 2^-s rounded to the E4M3 grid (to nearest: the hardware conversion), lo = what is left, on the same grid
+    int hw[2] = {0, 0}, lw[2] = {0, 0};
+    // (the half of the word a conversion writes or reads is part of the instruction: spelled out, not looped)
+#define MES_SPLIT_PAIR(E, W, UPPER)                                                                     \
+    {                                                                                                   \
+      const float s0 = xv[E] * inv, s1 = xv[E + 1] * inv;                                               \
+      hw[W] = __builtin_amdgcn_cvt_pk_fp8_f32(s0, s1, hw[W], UPPER);                                    \
+      const auto back = __builtin_amdgcn_cvt_pk_f32_fp8(hw[W], UPPER);                                  \
+      lw[W] = __builtin_amdgcn_cvt_pk_fp8_f32(s0 - back[0], s1 - back[1], lw[W], UPPER);                \
     }
+    MES_SPLIT_PAIR(0, 0, false)
+    MES_SPLIT_PAIR(2, 0, true)
+    MES_SPLIT_PAIR(4, 1, false)
+    MES_SPLIT_PAIR(6, 1, true)
+#undef MES_SPLIT_PAIR
     // columns 32 q + 8 i + e  ->  half = q / 2, lane group g = 2 (q % 2) + i / 2, bytes 8 (i % 2) + e
     const int lane = 16 * (2 * (q & 1) + (i >> 1)) + n;
     char* dst = stage + kStageFp8 + ((tt * 2 + 0) * 2 + (q >> 1)) * 1024 + lane * 16 + 8 * (i & 1);
-    *reinterpret_cast<u32x2*>(dst) = u32x2{hw[0], hw[1]};
-    *reinterpret_cast<u32x2*>(dst + 2048) = u32x2{lw[0], lw[1]};
+    *reinterpret_cast<u32x2*>(dst) = u32x2{(uint32_t)hw[0], (uint32_t)hw[1]};
+    *reinterpret_cast<u32x2*>(dst + 2048) = u32x2{(uint32_t)lw[0], (uint32_t)lw[1]};
     if (part == 0) {
       *reinterpret_cast<int*>(stage + kStageScale + (16 * tt + n) * 4) = 128 + s;
-      p.rowsum[c * kTokGroup + 16 * tt + n] = rs;
+      *reinterpret_cast<float*>(stage + kStageSum + (16 * tt + n) * 4) = rs;
     }
     return;
   }
-  // Salient activations of one visit as fp16 B operands.  Each token's values are divided by a power of
-  // two that puts the largest in [2^14, 2^15): the conversion bf16 -> fp16 is then exact for every value
-  // within 2^-29 of that largest one, and no value overflows.  The main loop multiplies back.
-  constexpr bool gather_role = true;
+  // Salient activations of one visit as B operands: block sb, lane 16 g + n holds x[token n of the tile][S[32 sb + 8 g + 0..7]]
+  // for the tokens of the tile that belong to the visit's expert, zero for the others and for ranks past k.
   const int gi = item - p.n_stage_items;
   const int li = gi / p.n_vis, v = gi - li * p.n_vis;
   const PerLinear& L = p.lin[li];
   const int a = p.vis_info[v] & 0xff, tt = p.vis_info[v] >> 8;
   const int32_t* si = L.sidx[a];
-  if (tid < 16) smax[tid] = 0;
-  __syncthreads();
-  const int lane = tid & 63, n = lane & 15;
-  const int tl = 16 * tt + n;
-  const bool inm = tl >= p.lo[a] && tl < p.hi[a];
-  const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
-  // Item i = (32-column block sb = i / 64, lane = i % 64) is one B-operand register set: eight gathered
-  // activations.  Up to kItems items per thread are gathered once and kept in registers across the
-  // per-token maximum (k <= 512); beyond that the values are gathered a second time.
-  constexpr int kItems = 4;
-  const int n_items = p.n_sb * 64;
-  const bool in_regs = n_items <= 256 * kItems;
-  uint32_t raw[kItems][4];   // two bf16 per word, as gathered
-  auto gather = [&](int i, uint32_t (&w)[4]) {
-    const int sb = i >> 6, gg = (i & 63) >> 4;
+  for (int i = tid; i < p.n_sb * 64; i += 256) {
+    const int sb = i >> 6, lane = i & 63, n = lane & 15, gg = lane >> 4;
+    const int tl = 16 * tt + n;
+    const bool inm = tl >= p.lo[a] && tl < p.hi[a];
+    const uint16_t* xrow = p.x + (size_t)(p.t0 + tl) * p.d_in;
+    u32x4 o;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int r0 = 32 * sb + 8 * gg + 2 * q;   // indices are clamped so that a corrupt list can never address outside the row
       uint32_t v0 = 0, v1 = 0;
       if (inm && r0 < p.k) v0 = xrow[min((uint32_t)si[r0], (uint32_t)(p.d_in - 1))];
       if (inm && r0 + 1 < p.k) v1 = xrow[min((uint32_t)si[r0 + 1], (uint32_t)(p.d_in - 1))];
-      w[q] = v0 | (v1 << 16);
+      o[q] = v0 | (v1 << 16);
     }
-  };
-  uint32_t mymax = 0;
-  float mysum = 0.0f;        // this thread's part of the token's sum over its salient columns
-  if (gather_role) {
-    if (in_regs) {
-#pragma unroll
-      for (int j = 0; j < kItems; ++j) {
-        const int i = tid + 256 * j;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) raw[j][q] = 0;
-        if (i < n_items) {
-          gather(i, raw[j]);
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            mymax = max(mymax, max(raw[j][q] & 0x7fffu, (raw[j][q] >> 16) & 0x7fffu));
-            mysum += bf16_to_f32((uint16_t)(raw[j][q] & 0xffffu)) + bf16_to_f32((uint16_t)(raw[j][q] >> 16));
-          }
-        }
-      }
-    } else if (inm) {
-      for (int r = tid >> 4; r < p.k; r += 16) {
-        const uint16_t xv = xrow[min((uint32_t)si[r], (uint32_t)(p.d_in - 1))];
-        mymax = max(mymax, (uint32_t)(xv & 0x7fffu));
-        mysum += bf16_to_f32(xv);
-      }
-    }
-    if (mymax) atomicMax(&smax[tid & 15], mymax);   // (tid & 15) == n: the same token
-  }
-  // the token's sum: its lanes of this wavefront (n, n + 16, n + 32, n + 48), then the four wavefronts in order
-  mysum += __shfl_xor(mysum, 16);
-  mysum += __shfl_xor(mysum, 32);
-  if (lane < 16) ssum[(tid >> 6) * 16 + lane] = mysum;
-  __syncthreads();
-  if (gather_role) {
-    int e = (int)(smax[n] >> 7) - 127 - 14;          // bf16 exponent field of the largest magnitude
-    if (smax[n] == 0) e = 0;
-    e = e < -110 ? -110 : (e > 110 ? 110 : e);
-    const float inv = __uint_as_float((uint32_t)(127 - e) << 23);
-    if (inm && tid < 16) {
-      L.sal_scale[tl] = __uint_as_float((uint32_t)(127 + e) << 23);
-      L.sal_sum[tl] = ((ssum[n] + ssum[16 + n]) + ssum[32 + n]) + ssum[48 + n];
-    }
-    auto convert_store = [&](int i, const uint32_t (&w)[4]) {
-      u32x4 o;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float v0 = bf16_to_f32((uint16_t)(w[q] & 0xffffu)) * inv, v1 = bf16_to_f32((uint16_t)(w[q] >> 16)) * inv;
-        o[q] = (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v0) | ((uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v1) << 16);
-      }
-      L.xs[((size_t)v * p.n_sb + (i >> 6)) * 64 + (i & 63)] = o;
-    };
-    if (in_regs) {
-#pragma unroll
-      for (int j = 0; j < kItems; ++j)
-        if (tid + 256 * j < n_items) convert_store(tid + 256 * j, raw[j]);
-    } else {
-      for (int i = tid; i < n_items; i += 256) {
-        uint32_t w[4];
-        gather(i, w);
-        convert_store(i, w);
-      }
-    }
+    L.xs[((size_t)v * p.n_sb + sb) * 64 + lane] = o;
   }
 }
 
@@ -380,10 +297,6 @@ __global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void global_void;
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ f32x4 mfma_f16(u32x4 a, u32x4 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
 
 // Loads are written as (wave-uniform pointer) + (32-bit unsigned lane offset): the pointer then lives in
 // scalar registers and one vector register per lane serves every stream.
@@ -394,12 +307,7 @@ __device__ __forceinline__ global_char* gptr(const void* q) { return reinterpret
 __device__ __forceinline__ u32x4 ld128(const void* uniform_ptr, uint32_t lane_off) {
   return *reinterpret_cast<__attribute__((address_space(1))) const u32x4*>(gptr(uniform_ptr) + lane_off);
 }
-__device__ __forceinline__ int ld32i(const void* uniform_ptr, uint32_t lane_off) {
-  return *reinterpret_cast<__attribute__((address_space(1))) const int*>(gptr(uniform_ptr) + lane_off);
-}
-__device__ __forceinline__ float ld32f(const void* uniform_ptr, uint32_t lane_off) {
-  return *reinterpret_cast<__attribute__((address_space(1))) const float*>(gptr(uniform_ptr) + lane_off);
-}
+
 
 __device__ __forceinline__ u32x4 lds128(const char* stage, int off) { return *reinterpret_cast<const u32x4*>(stage + off); }
 
@@ -416,13 +324,14 @@ __device__ __forceinline__ v8i lds_fp8(const char* stage, int tt, int piece, int
 // LDS access of the wavefront wait for these copies, i.e. stall each chunk for a full memory round trip,
 // because it cannot tell that they go to the stage nobody reads yet.  stage_barrier() does the waiting.
 template <int NW>
-__device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, int wave, int lane) {
+__device__ __forceinline__ void stage_copy(const char* src, char* dst_lds, char* dst_extra, int wave, int lane) {
 #pragma unroll
   for (int i = 0; i < (kStageBlocks + NW - 1) / NW; ++i) {
     const int blk = wave + NW * i;
-    if (kStageBlocks % NW != 0 && blk >= kStageBlocks) break;   // 32 blocks dealt round-robin: some wavefronts carry one more
+    if (kStageBlocks % NW != 0 && blk >= kStageBlocks) break;   // 33 blocks dealt round-robin: some wavefronts carry one more
     const char* g = src + blk * 1024;                                 // scalar base; the lanes add 16 * lane
-    const uint32_t l = (uint32_t)(uintptr_t)(dst_lds + blk * 1024);   // LDS byte address; the hardware adds 16 * lane
+    // LDS byte address (the hardware adds 16 * lane): the operand images, or the block of per-token numbers
+    const uint32_t l = (uint32_t)(uintptr_t)(blk < 32 ? dst_lds + blk * 1024 : dst_extra);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"((uint32_t)lane * 16u), "s"(g), "s"(l) : "memory", "m0");
   }
 }
@@ -487,7 +396,6 @@ struct Stream {
   int a0 = 0;
   // launch constants (see keep())
   const char* xt;             // the activation stages
-  const float* rowsum;
   const char* xs;             // this linear's gathered salient activations
   const char* base_at;        // this row tile's base block of chunk 0
   uint32_t base_stride, code_stride;   // bytes from one chunk's block of this row tile to the next chunk's
@@ -497,8 +405,7 @@ struct Stream {
   const int* vis_lds;         // LDS copy of the visit table
   const uint64_t* sal_lds;    // LDS: per slot, this linear's salient tile of that expert
   uint32_t slot_tok[TT];
-  float rs_acc = 0.0f, rs_in[2];   // lane = token: sum of its activations over the chunks done so far / of the current, next chunk
-  int scale[2][TT];           // per-token block scales of the current / next chunk
+  float rs_acc = 0.0f;        // lane = token: sum of its activations over the chunks done so far
   u32x4 base[2][4];
   u32x4 code[2][NL];
   f32x4 acc_base[TT], acc_raw[TT];
@@ -507,21 +414,22 @@ struct Stream {
   // (pairs sp, sp + nsplit, ... of n_vis * n_sb) are dealt kSalPerChunk to a chunk, requested one chunk before
   // they are multiplied.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
   static constexpr int kSalPerChunk = 1;
-  const float2* tok;   // LDS, per token: .x sum over its salient columns, .y the power of two its salient activations were divided by
+  const float* step_w;   // LDS: this wavefront's steps, [slot][16 rows]
+  float z;
   u32x4 sal_x[kSalPerChunk], sal_d[kSalPerChunk];
-  int sal_tt[kSalPerChunk];
+  int sal_tt[kSalPerChunk], sal_slot[kSalPerChunk];
   int sal_v, sal_sb, sal_left;   // (visit, block) of the next pair to request; pairs not yet requested
   bool nx_more;                  // the request being prepared: is there a pair, its visit entry, its addresses
   int nx_info_v;                 // (as read from LDS: the same in every lane)
-  int nx_tt;
+  int nx_tt, nx_slot;
   uint64_t nx_sal_v;
   uint32_t nx_xoff, nx_doff;
 
   __device__ __forceinline__ Stream(const LinearParams& p_, const PerLinear& L_, int lane_, int jt_, char* park_,
-                                    const float2* tok_, const int* vis_lds_, const uint64_t* sal_lds_, int rev_)
-      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), rev(rev_), parkp(park_), vis_lds(vis_lds_), sal_lds(sal_lds_), tok(tok_) {
+                                    const float* step_w_, const int* vis_lds_, const uint64_t* sal_lds_, int rev_)
+      : p(p_), L(L_), lane(lane_), n(lane_ & 15), jt(jt_), rev(rev_), parkp(park_), vis_lds(vis_lds_), sal_lds(sal_lds_), step_w(step_w_) {
+    z = keep(p.z);
     xt = keep(p.xt);
-    rowsum = keep(p.rowsum);
     xs = keep(reinterpret_cast<const char*>(L.xs));
     base_at = keep(L.w_base + (size_t)jt * 4096);
     base_stride = keep((uint32_t)L.n_jt * 4096u);
@@ -580,6 +488,7 @@ struct Stream {
   __device__ __forceinline__ void sal_address() {
     const int info = __builtin_amdgcn_readfirstlane(nx_info_v);
     nx_tt = nx_more ? info >> 8 : -1;
+    nx_slot = info & 0xff;
     nx_sal_v = sal_lds[info & 0xff];
     nx_xoff = ((uint32_t)sal_v * (uint32_t)n_sb + (uint32_t)sal_sb) * 1024u;
     nx_doff = ((uint32_t)jt * (uint32_t)n_sb + (uint32_t)sal_sb) * 1024u;
@@ -591,8 +500,9 @@ struct Stream {
   }
   // Always two loads, so that the number of loads in flight does not depend on the data: once the pairs are
   // used up both read the start of the activation stages and tt_out = -1.
-  __device__ __forceinline__ void sal_issue(u32x4& x, u32x4& d, int& tt_out) {
+  __device__ __forceinline__ void sal_issue(u32x4& x, u32x4& d, int& tt_out, int& slot_out) {
     tt_out = nx_tt;
+    slot_out = nx_slot;
     const bool more = nx_tt >= 0;
     // the tile pointer was read from LDS a good while ago and is the same in every lane: into scalar registers with it
     const uint64_t tile = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(nx_sal_v >> 32)) << 32) |
@@ -601,19 +511,31 @@ struct Stream {
     d = ld128(more ? reinterpret_cast<const char*>(tile) + nx_doff : xt, (uint32_t)lane * 16u);
   }
 
-  // The pair's 16 x 16 product goes to the base accumulators of its token tile, times the tokens' scale.  Which
-  // tile that is is known only at run time; rather than branch around four matrix instructions (which makes
-  // the compiler keep two copies of every accumulator), the product is formed once and added everywhere with
-  // a factor that is zero for the other tiles.
+  // The pair's 16 x 16 product goes to the base accumulators of its token tile.  Its weights are D + z step (see the
+  // top of the file), formed in fp32 from the fp16 values and the row's step and written as the sum of two bf16
+  // numbers.  Which tile the product belongs to is known only at run time; rather than branch around the matrix
+  // instructions (which makes the compiler keep two copies of every accumulator), the product is formed once and
+  // added to the tile it belongs to through a select.
   __device__ __forceinline__ void sal_multiply(int i) {
-    const f32x4 t = mfma_f16(sal_d[i], sal_x[i], f32x4{0, 0, 0, 0});
+    const f16x8 dh = __builtin_bit_cast(f16x8, sal_d[i]);
+    const float zs = z * step_w[sal_slot[i] * 16 + (lane & 15)];
+    u32x4 hi, lo;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float f0 = (float)dh[2 * q] + zs, f1 = (float)dh[2 * q + 1] + zs;
+      const uint32_t h = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{f0, f1}, bf16x2));   // round to nearest even
+      const float r0 = f0 - __uint_as_float(h << 16), r1 = f1 - __uint_as_float(h & 0xffff0000u);
+      hi[q] = h;
+      lo[q] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{r0, r1}, bf16x2));
+    }
+    f32x4 t = mfma_bf16(hi, sal_x[i], f32x4{0, 0, 0, 0});
+    t = mfma_bf16(lo, sal_x[i], t);
     const int stt = sal_tt[i];
-    const float ss = stt >= 0 ? tok[16 * (stt >= 0 ? stt : 0) + n].y : 0.0f;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-      const float m = pt(tt) == stt ? ss : 0.0f;
+      const bool mine = pt(tt) == stt;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) acc_base[tt][v] += t[v] * m;
+      for (int v = 0; v < 4; ++v) acc_base[tt][v] += mine ? t[v] : 0.0f;
     }
   }
 
@@ -623,16 +545,6 @@ struct Stream {
 #pragma unroll
     for (int kb = 0; kb < 4; ++kb) base[BUF][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
   }
-
-  template <int BUF>
-  __device__ __forceinline__ void load_scales(int c) {
-    const char* src = xt + (size_t)c * kStageBytes + kStageScale;
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) scale[BUF][tt] = ld32i(src + 64 * pt(tt), (uint32_t)n * 4u);
-  }
-
-  template <int BUF>
-  __device__ __forceinline__ void load_rowsum(int c) { rs_in[BUF] = ld32f(rowsum + c * kTokGroup, (uint32_t)lane * 4u); }
 
   template <int BUF>
   __device__ __forceinline__ void load_code_regs(int c) {
@@ -652,7 +564,7 @@ struct Stream {
   }
 
   // Tile tt's share of the requests of one chunk: code words of chunk c2 (two ahead) into the register buffer
-  // that was just parked, base weights and scales of chunk cn (one ahead) into the other base buffer.
+  // that was just parked, base weights of chunk cn (one ahead) into the other base buffer.
   template <int BUF, bool NOBASE>
   __device__ __forceinline__ void request_share(int tt, int cn, int c2) {
     const uint32_t off = (uint32_t)c2 * code_stride;
@@ -665,9 +577,6 @@ struct Stream {
       for (int kb = 0; kb < 4; ++kb)
         if (kb * TT / 4 == tt) base[BUF ^ 1][kb] = ld128(src + kb * 1024, (uint32_t)lane * 16u);
     }
-    scale[BUF ^ 1][tt] = ld32i(xt + (size_t)cn * kStageBytes + kStageScale + 64 * pt(tt), (uint32_t)n * 4u);
-    if constexpr (!NOBASE)
-      if (tt == 0) rs_in[BUF ^ 1] = ld32f(rowsum + cn * kTokGroup, (uint32_t)lane * 4u);
   }
 
   __device__ __forceinline__ CodeRegs<BITS> parked(int a) const {
@@ -677,15 +586,15 @@ struct Stream {
   }
 
   // Loads of one chunk() call that are younger than its stage copy: all of its weight and scale requests.
-  template <bool NOBASE> static constexpr int younger() { return NL + (NOBASE ? 0 : 5) + TT + 2 * kSalPerChunk; }
+  template <bool NOBASE> static constexpr int younger() { return NL + (NOBASE ? 0 : 4) + 2 * kSalPerChunk; }
 
-  // One chunk out of base / scale buffer BUF and stage `cur`; the next chunks' data are requested first.
-  // NOBASE: a sweep after the first -- the base product is done, only the slots of this sweep are multiplied.
+  // One chunk out of base buffer BUF and stage `cur` (its per-token numbers: cur_x); the next chunks' data are
+  // requested first.  NOBASE: a sweep after the first -- the base product is done, only the slots of this sweep are multiplied.
   template <int BUF, bool NOBASE>
-  __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, char* nxt, int wave) {
-    stage_copy<NW>(xt + (size_t)cn * kStageBytes, nxt, wave, lane);
+  __device__ __forceinline__ void chunk(int cn, int c2, const char* cur, const char* cur_x, char* nxt, char* nxt_x, int wave) {
+    stage_copy<NW>(xt + (size_t)cn * kStageBytes, nxt, nxt_x, wave, lane);
     sal_lookup();
-    if constexpr (!NOBASE) rs_acc += rs_in[BUF];   // this chunk's share of the tokens' sums (requested a chunk ago)
+    if constexpr (!NOBASE) rs_acc += *reinterpret_cast<const float*>(cur_x + 256 + lane * 4);   // this chunk's share of the tokens' sums
     // Order inside a tile: the low-bit visits first (operands bhi / blo, read from LDS during the previous
     // tile's base product), then the base product (operands xb, read while the visits ran).  Every LDS read is
     // thereby issued a good stretch of arithmetic before its data are needed.
@@ -698,6 +607,7 @@ struct Stream {
       request_share<BUF, NOBASE>(tt, cn, c2);
       const int last = tlast[tt];
       int a = tfirst[tt];
+      const int scale = *reinterpret_cast<const int*>(cur_x + 64 * pt(tt) + n * 4);   // the tokens' block scales for this chunk
       CodeRegs<BITS> cr = parked(a);
       u32x4 xb[4];
       if constexpr (!NOBASE) {
@@ -705,7 +615,7 @@ struct Stream {
         for (int kb = 0; kb < 4; ++kb) xb[kb] = lds128(cur, (kb * 4 + pt(tt)) * 1024 + lane * 16);
       }
       do {
-        const int sc = slot_tok[tt] == (uint32_t)(a + a0) ? scale[BUF][tt] : 0;
+        const int sc = slot_tok[tt] == (uint32_t)(a + a0) ? scale : 0;
         const u32x4 d = dequant_lo<BITS>(cr);
         u32x4 h;
         if constexpr (BITS >= 3) h = dequant_hi(cr);
@@ -722,7 +632,7 @@ struct Stream {
     }
     static_assert(kSalPerChunk == 1, "one pair per chunk: the request steps above prepare exactly one");
     sal_multiply(0);
-    sal_issue(sal_x[0], sal_d[0], sal_tt[0]);
+    sal_issue(sal_x[0], sal_d[0], sal_tt[0], sal_slot[0]);
     // The next chunk's code words (requested during the previous chunk) go to this wavefront's LDS area now:
     // its visits of this chunk are over, the area is its own, and the wavefronts get here at slightly
     // different times -- the 64 KiB of LDS writes spread out and fill what would be waiting at the barrier.
@@ -748,24 +658,27 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
 
   // One LDS block carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
   // offset field of the LDS instructions, so one lane-offset register serves every operand read.
-  //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | parked code words, one private area per wavefront |
-  //   per wavefront and slot the 16 steps | per token (salient sum, salient scale) | visit table | salient tile table
+  //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | the stages' blocks of per-token numbers, 1 KiB each |
+  //   parked code words, one private area per wavefront |
+  //   per wavefront and slot the 16 steps | visit table | salient tile table
   constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
   constexpr int kLaunchSlots = NA == 4 ? 4 : kMaxSlots;   // experts of one launch; NA of them per sweep
   constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
   constexpr int kVisBytes = (kMaxVisits + 1 + 3) / 4 * 16;
-  __shared__ __attribute__((aligned(16))) char lds[2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes + kMaxSlots * 8 + 256];
+  constexpr int kStages = 2 * kStageLds + 2048;
+  __shared__ __attribute__((aligned(16))) char lds[kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8 + 256];
   char* const stage0 = lds;
   char* const stage1 = lds + kStageLds;
-  char* const park_all = lds + 2 * kStageLds;
-  float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + 2 * kStageLds + kParkBytes);
-  float2* const tok_lds = reinterpret_cast<float2*>(lds + 2 * kStageLds + kParkBytes + kStepBytes);
-  int* const vis_lds = reinterpret_cast<int*>(lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8);
-  uint64_t* const sal_lds = reinterpret_cast<uint64_t*>(lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes);
-  char* const warm_lds = lds + 2 * kStageLds + kParkBytes + kStepBytes + kTokGroup * 8 + kVisBytes + kMaxSlots * 8;   // 256 bytes nobody reads
+  char* const extra0 = lds + 2 * kStageLds;
+  char* const extra1 = lds + 2 * kStageLds + 1024;
+  char* const park_all = lds + kStages;
+  float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + kStages + kParkBytes);
+  int* const vis_lds = reinterpret_cast<int*>(lds + kStages + kParkBytes + kStepBytes);
+  uint64_t* const sal_lds = reinterpret_cast<uint64_t*>(lds + kStages + kParkBytes + kStepBytes + kVisBytes);
+  char* const warm_lds = lds + kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8;   // 256 bytes nobody reads
 
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), tok_lds, vis_lds, sal_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), &step_lds[wave][0][0], vis_lds, sal_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -789,28 +702,22 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
                  : : "v"(g), "s"((uint32_t)(uintptr_t)warm_lds) : "memory", "m0");
   }
   // first chunks' weights and activations: requested now
-  stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
+  stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, extra0, wave, lane);
   ws.template load_base<0>(chunk_at(0));
-  ws.template load_scales<0>(chunk_at(0));
-  ws.template load_rowsum<0>(chunk_at(0));
   ws.template load_code_regs<0>(chunk_at(0));
   ws.template load_code_regs<1>(chunk_at(1));
-  // What the epilogue needs -- every slot's step for this wavefront's 16 output channels, and per token the sum
-  // over its salient columns (subtracted by the first split only: it belongs to the whole column range) and the
-  // salient scale -- is fetched now and kept in LDS until then: in registers it would be live across the whole
-  // stream.  Likewise the two tables of the salient requests.
+  // Every slot's step for this wavefront's 16 output channels (for the salient weights and the epilogue) is fetched
+  // now and kept in LDS: in registers it would be live across the whole stream.  Likewise the two tables of the
+  // salient requests.
   const int st_a = lane >> 2, st_j = 16 * jt + 4 * (lane & 3);
   f32x4 st_v = {0, 0, 0, 0};
   if (st_a < kLaunchSlots && st_a < p.n_act && st_j < L.d_out) st_v = *reinterpret_cast<const f32x4*>(L.step[st_a] + st_j);
-  float2 tok_v = {0.0f, 0.0f};
-  if (tid < kTokGroup && p.n_vis > 0) tok_v = float2{sp == 0 ? L.sal_sum[tid] : 0.0f, L.sal_scale[tid]};
   int vis_v = 0;
   uint64_t sal_v = 0;
   if (tid <= kMaxVisits) vis_v = p.vis_info[tid];
   if (tid < kMaxSlots) sal_v = reinterpret_cast<uint64_t>(L.sal[tid]);
   ws.sal_begin(sp);
   if (st_a < kLaunchSlots) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
-  if (tid < kTokGroup) tok_lds[tid] = tok_v;
   if (tid <= kMaxVisits) vis_lds[tid] = vis_v;
   if (tid < kMaxSlots) sal_lds[tid] = sal_v;
 
@@ -822,32 +729,31 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   while (ws.sal_left > S::kSalPerChunk * len * n_sweeps) {
     ws.sal_lookup();
     ws.sal_address();
-    ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
+    ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0], ws.sal_slot[0]);
     ws.sal_multiply(0);
   }
   ws.sal_lookup();
   ws.sal_address();
-  ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0]);
+  ws.sal_issue(ws.sal_x[0], ws.sal_d[0], ws.sal_tt[0], ws.sal_slot[0]);
   for (int i = 0; i < len; i += 2) {
-    ws.template chunk<0, false>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave);
+    ws.template chunk<0, false>(chunk_at(i + 1), chunk_at(i + 2), stage0, extra0, stage1, extra1, wave);
     if (i + 1 >= len) break;
-    ws.template chunk<1, false>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+    ws.template chunk<1, false>(chunk_at(i + 2), chunk_at(i + 3), stage1, extra1, stage0, extra0, wave);
   }
   // Further sweeps over the same chunks for the slots beyond the first NA: activations again (from L2), these
   // slots' code words, no base weights.  The last barrier of the sweep before has every wavefront done with
   // both stages.
   for (int sweep = 1; sweep < n_sweeps; ++sweep) {
     ws.begin_sweep(sweep * NA);
-    stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, wave, lane);
-    ws.template load_scales<0>(chunk_at(0));
+    stage_copy<NW>(ws.xt + (size_t)chunk_at(0) * kStageBytes, stage0, extra0, wave, lane);
     ws.template load_code_regs<0>(chunk_at(0));
     ws.template load_code_regs<1>(chunk_at(1));
     ws.template park<0>();
     stage_barrier<0>();
     for (int i = 0; i < len; i += 2) {
-      ws.template chunk<0, true>(chunk_at(i + 1), chunk_at(i + 2), stage0, stage1, wave);
+      ws.template chunk<0, true>(chunk_at(i + 1), chunk_at(i + 2), stage0, extra0, stage1, extra1, wave);
       if (i + 1 >= len) break;
-      ws.template chunk<1, true>(chunk_at(i + 2), chunk_at(i + 3), stage1, stage0, wave);
+      ws.template chunk<1, true>(chunk_at(i + 2), chunk_at(i + 3), stage1, extra1, stage0, extra0, wave);
     }
   }
 
@@ -860,8 +766,8 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   for (int tt = 0; tt < TT; ++tt) {
     f32x4 stepv = {0, 0, 0, 0};
     if (slot_tok[tt] != 0xffu) stepv = *reinterpret_cast<const f32x4*>(&step_lds[wave][slot_tok[tt]][4 * g]);
-    // zero point: z (sum over this workgroup's columns - sum over the token's salient columns)
-    const float corr = p.z * (__shfl(ws.rs_acc, 16 * ws.pt(tt) + n) - tok_lds[16 * ws.pt(tt) + n].x);
+    // zero point: z times the token's sum over this workgroup's columns (lane = token in rs_acc)
+    const float corr = p.z * __shfl(ws.rs_acc, 16 * ws.pt(tt) + n);
 #pragma unroll
     for (int v = 0; v < 4; ++v)
       o[tt][v] = acc_base[tt][v] + stepv[v] * (acc_raw[tt][v] - corr);
@@ -949,7 +855,7 @@ Plan plan_for(int d_in, const int* d_out, int n_linears) {
 }
 
 struct WorkspaceLayout {
-  size_t xt, rowsum, per_linear[kMaxLinears], partial, total;   // per linear: xs, then the tokens' salient sums and scales
+  size_t xt, per_linear[kMaxLinears], partial, total;   // per linear: xs
   size_t xs_bytes;
 };
 
@@ -961,11 +867,10 @@ WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
   WorkspaceLayout w;
   size_t off = 0;
   w.xt = off;      off += (size_t)(pi / kChunk) * kStageBytes;
-  w.rowsum = off;  off += (size_t)(pi / kChunk) * kTokGroup * 4;
   w.xs_bytes = (size_t)kMaxVisits * (ceil_to(d_in, kSalPad) / 32) * 1024;   // k <= d_in
   for (int l = 0; l < kMaxLinears; ++l) {
     w.per_linear[l] = off;
-    if (l < n_linears) off += w.xs_bytes + 512;
+    if (l < n_linears) off += w.xs_bytes;
   }
   w.partial = off; off += pl.nsplit > 1 ? (size_t)rgs * pl.nsplit * 4 * (64 * pl.nw) * 16 : 0;
   w.total = off;
@@ -1030,7 +935,6 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   LinearParams p;
   p.x = reinterpret_cast<const uint16_t*>(c.x);
   p.xt = ws + wl.xt;
-  p.rowsum = reinterpret_cast<float*>(ws + wl.rowsum);
   p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
   const int pi = ceil_to(d0.d_in, kColPad);
   p.d_in = d0.d_in;
@@ -1048,8 +952,6 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     L.w_base = reinterpret_cast<const char*>(c.lin[ll].w_base_tiled);
     L.y = reinterpret_cast<uint16_t*>(c.lin[ll].y);
     L.xs = reinterpret_cast<u32x4*>(ws + wl.per_linear[ll]);
-    L.sal_sum = reinterpret_cast<float*>(ws + wl.per_linear[ll] + wl.xs_bytes);
-    L.sal_scale = L.sal_sum + kTokGroup;
     L.d_out = d_outs[ll];
     L.n_jt = ceil_to(d_outs[ll], kRowPad) / 16;
     L.rg_begin = rgs;
