@@ -95,6 +95,24 @@ struct LinearParams {
   float z;
 };
 
+// One launch serves up to kMaxGroups token groups (256 tokens), in two classes: the groups with many experts (their
+// workgroups take about half as long again as the others') come first in g[] and in the workgroup ids, so that the
+// long workgroups start first and the short ones fill the compute units behind them -- in the order of the token
+// groups the last workgroups to start would be long ones, with most of the chip idle while they finish.
+// Within a class the ids are laid out so that the workgroups of one row group -- one per token group -- are
+// neighbours on one XCD: they start together, stream the same base weights at about the same time, and all but the
+// first find them in that XCD's L2.  Memory sees the base weights once per class rather than once per token group.
+constexpr int kMaxGroups = 4;
+struct LaunchParams {
+  LinearParams g[kMaxGroups];
+  int n_groups;
+  int n_first;  // groups of the first class (g[0 .. n_first)), at least 1
+  int rgs;      // row groups of the launch (all linears)
+  int rg8;      // ... in eights, rounded up
+  int wg_per_group;   // rg8 * 8 * nsplit.  Flat workgroup id within a class of m groups:
+                      // ((split * rg8 + rg / 8) * m + group) * 8 + rg % 8
+};
+
 // The linear a row group belongs to.
 __device__ __forceinline__ int linear_of(const LinearParams& p, int rg) {
   int l = 0;
@@ -207,8 +225,10 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_floa
 //                         factor two undoes the fp4 codes' u / 2)
 //   bytes [33024, 33280)  float [64]: sum of the token's activations over the chunk's columns; the rest of the
 //                         33rd KiB is padding
-__global__ __launch_bounds__(256) void k_prepare(const LinearParams p) {
+__global__ __launch_bounds__(256) void k_prepare(const LaunchParams mp) {
+  const LinearParams& p = mp.g[blockIdx.y];
   const int tid = threadIdx.x, item = blockIdx.x;
+  if (item >= p.n_items) return;   // the grid is as wide as the group with the most items
   if (item < p.n_stage_items) {
     // (chunk c, token tile tt): thread = (token n of the tile, 8 columns `part` of the chunk's 128)
     const int c = item / p.tiles, tt = item - c * p.tiles;
@@ -641,32 +661,43 @@ struct Stream {
   }
 };
 
+// Active experts one sweep handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
+// 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
+constexpr int max_pass_slots(int bits) { return bits >= 3 ? 8 : 16; }
+
+// LDS of a workgroup, carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
+// offset field of the LDS instructions, so one lane-offset register serves every operand read.
+//   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | the stages' blocks of per-token numbers, 1 KiB each |
+//   parked code words, one private area per wavefront |
+//   per wavefront and slot the 16 steps | visit table | salient tile table | 256 bytes nobody reads
+template <int BITS, int NA, int NW>
+struct LdsPlan {
+  static constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
+  static constexpr int kLaunchSlots = NA == 4 ? 4 : kMaxSlots;   // experts of one group; NA of them per sweep
+  static constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
+  static constexpr int kVisBytes = (kMaxVisits + 1 + 3) / 4 * 16;
+  static constexpr int kStages = 2 * kStageLds + 2048;
+  static constexpr int kTotal = kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8 + 256;
+};
+
+// One workgroup's work: row group rg, column split sp of token group p, with NA expert slots per sweep.
 template <int BITS, int TT, int NA, int NW>
-__global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) {
+__device__ __forceinline__ void stream_rows(const LinearParams& p, char* lds, int rg, int sp) {
   const int tid = threadIdx.x, lane = tid & 63;
   // The wavefront index is the same in all 64 lanes; saying so keeps every value derived from it in scalar
   // registers and every branch on them a scalar branch.  MFMA ignores the EXEC mask, so an MFMA must never
   // sit in a region the compiler predicates with EXEC instead of branching around.
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
-  const int rg = blockIdx.x, sp = blockIdx.y;
   const PerLinear& L = p.lin[linear_of(p, rg)];
   int jt = (rg - L.rg_begin) * NW + wave;
   const bool live = jt < L.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
   jt = live ? jt : L.n_jt - 1;
   const int c_begin = p.c_split[sp], c_end = p.c_split[sp + 1];
 
-  // One LDS block carved up by hand, the two activation stages first: below 64 KiB their addresses fit the
-  // offset field of the LDS instructions, so one lane-offset register serves every operand read.
-  //   [0, 32 KiB) stage 0 | [32, 64 KiB) stage 1 | the stages' blocks of per-token numbers, 1 KiB each |
-  //   parked code words, one private area per wavefront |
-  //   per wavefront and slot the 16 steps | visit table | salient tile table
-  constexpr int kParkBytes = NW * NA * code_block_bytes(BITS);
-  constexpr int kLaunchSlots = NA == 4 ? 4 : kMaxSlots;   // experts of one launch; NA of them per sweep
-  constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
-  constexpr int kVisBytes = (kMaxVisits + 1 + 3) / 4 * 16;
-  constexpr int kStages = 2 * kStageLds + 2048;
-  __shared__ __attribute__((aligned(16))) char lds[kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8 + 256];
+  using Plan = LdsPlan<BITS, NA, NW>;
+  constexpr int kParkBytes = Plan::kParkBytes, kLaunchSlots = Plan::kLaunchSlots, kStepBytes = Plan::kStepBytes;
+  constexpr int kVisBytes = Plan::kVisBytes, kStages = Plan::kStages;
   char* const stage0 = lds;
   char* const stage1 = lds + kStageLds;
   char* const extra0 = lds + 2 * kStageLds;
@@ -675,7 +706,7 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + kStages + kParkBytes);
   int* const vis_lds = reinterpret_cast<int*>(lds + kStages + kParkBytes + kStepBytes);
   uint64_t* const sal_lds = reinterpret_cast<uint64_t*>(lds + kStages + kParkBytes + kStepBytes + kVisBytes);
-  char* const warm_lds = lds + kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8;   // 256 bytes nobody reads
+  char* const warm_lds = lds + kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8;
 
   using S = Stream<BITS, TT, NA, NW>;
   S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), &step_lds[wave][0][0], vis_lds, sal_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
@@ -794,10 +825,33 @@ __global__ __launch_bounds__(64 * NW) void k_delta_linear(const LinearParams p) 
   }
 }
 
+// The kernel: finds its (row group, column split, token group) and runs it with as few expert slots per sweep as
+// the group needs -- a group whose tokens belong to four experts or fewer (most groups of a batch that is sorted by
+// expert) moves a quarter of the code words of a full one through registers and LDS.
+// CLASSES: 0 = every group of the launch is such a short one, 1 = none is, 2 = both kinds (the workgroup looks).
+template <int BITS, int TT, int NW, int CLASSES>
+__global__ __launch_bounds__(64 * NW) void k_delta_linear(const LaunchParams mp) {
+  constexpr int NA = max_pass_slots(BITS);
+  __shared__ __attribute__((aligned(16))) char lds[LdsPlan<BITS, CLASSES == 0 ? 4 : NA, NW>::kTotal];
+  // flat workgroup id -> (class, split, row group, token group), see LaunchParams; ids go round-robin to the XCDs
+  const int first_wgs = mp.n_first * mp.wg_per_group;
+  const bool second = (int)blockIdx.x >= first_wgs;
+  const int b = second ? blockIdx.x - first_wgs : blockIdx.x, m = second ? mp.n_groups - mp.n_first : mp.n_first;
+  const int bq = b >> 3, bq2 = bq / m;
+  const int rg = (bq2 % mp.rg8) * 8 + (b & 7), sp = bq2 / mp.rg8;
+  if (rg >= mp.rgs) return;   // padding of the row groups to a multiple of eight
+  const LinearParams& p = mp.g[(second ? mp.n_first : 0) + bq - bq2 * m];
+  if constexpr (CLASSES == 0) stream_rows<BITS, TT, 4, NW>(p, lds, rg, sp);
+  else if constexpr (CLASSES == 1) stream_rows<BITS, TT, NA, NW>(p, lds, rg, sp);
+  else if (p.n_act <= 4) stream_rows<BITS, TT, 4, NW>(p, lds, rg, sp);
+  else stream_rows<BITS, TT, NA, NW>(p, lds, rg, sp);
+}
+
 // Split columns only: y = sum over splits (in split order) of the fp32 partial tiles, rounded to bf16.  One
 // workgroup per (row group, token tile), threads laid out as in the main kernel.
 template <int NW>
-__global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p) {
+__global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LaunchParams mp) {
+  const LinearParams& p = mp.g[blockIdx.z];
   constexpr int NT = 64 * NW;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
   const int rg = blockIdx.x, tt = blockIdx.y;
@@ -814,10 +868,6 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LinearParams p)
     *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
   }
 }
-
-// Active experts one launch handles: their code words for one chunk are parked in LDS (8 wavefronts x slots x
-// 256 b bytes next to the two activation stages must fit the 160 KiB of a compute unit).
-constexpr int max_pass_slots(int bits) { return bits >= 3 ? 8 : 16; }
 
 // Wavefronts per workgroup (each owns 16 output channels): 8 fill a compute unit's four SIMDs two deep; 7 or 6
 // are chosen when that makes the number of workgroups fit the 256 compute units better.
@@ -854,8 +904,9 @@ Plan plan_for(int d_in, const int* d_out, int n_linears) {
   return best;
 }
 
+// The workspace of one token group; a launch of n groups uses n of these, one after the other.
 struct WorkspaceLayout {
-  size_t xt, per_linear[kMaxLinears], partial, total;   // per linear: xs
+  size_t xt, per_linear[kMaxLinears], partial, total;   // per linear: xs; total is a multiple of 256
   size_t xs_bytes;
 };
 
@@ -873,40 +924,45 @@ WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
     if (l < n_linears) off += w.xs_bytes;
   }
   w.partial = off; off += pl.nsplit > 1 ? (size_t)rgs * pl.nsplit * 4 * (64 * pl.nw) * 16 : 0;
-  w.total = off;
+  w.total = (off + 255) / 256 * 256;
   return w;
 }
 
-template <int BITS, int NA, int NW>
-hipError_t launch_tt(const LinearParams& p, int tt, dim3 grid, hipStream_t s) {
-  switch (tt) {
-    case 1: k_delta_linear<BITS, 1, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
-    case 2: k_delta_linear<BITS, 2, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
-    default: k_delta_linear<BITS, 4, NA, NW><<<grid, 64 * NW, 0, s>>>(p); break;
+// Token groups a workspace sized for `max_tokens` holds.
+inline int groups_for(int max_tokens) { return max_tokens <= kTokGroup ? 1 : max_tokens <= 2 * kTokGroup ? 2 : kMaxGroups; }
+
+template <int BITS, int NW>
+hipError_t launch_tt(const LaunchParams& mp, int tt, int classes, int grid, hipStream_t s) {
+  if (classes == 2) {   // both kinds of groups: built for four token tiles only (fewer tiles are a special case of it)
+    k_delta_linear<BITS, 4, NW, 2><<<grid, 64 * NW, 0, s>>>(mp);
+    return hipGetLastError();
+  }
+  switch (tt * 2 + classes) {
+    case 2: k_delta_linear<BITS, 1, NW, 0><<<grid, 64 * NW, 0, s>>>(mp); break;
+    case 3: k_delta_linear<BITS, 1, NW, 1><<<grid, 64 * NW, 0, s>>>(mp); break;
+    case 4: k_delta_linear<BITS, 2, NW, 0><<<grid, 64 * NW, 0, s>>>(mp); break;
+    case 5: k_delta_linear<BITS, 2, NW, 1><<<grid, 64 * NW, 0, s>>>(mp); break;
+    case 8: k_delta_linear<BITS, 4, NW, 0><<<grid, 64 * NW, 0, s>>>(mp); break;
+    default: k_delta_linear<BITS, 4, NW, 1><<<grid, 64 * NW, 0, s>>>(mp); break;
   }
   return hipGetLastError();
 }
 
-template <int BITS, int NA>
-hipError_t launch_nw(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
+template <int BITS>
+hipError_t launch_nw(const LaunchParams& mp, int tt, int classes, int nw, int grid, hipStream_t s) {
   switch (nw) {
-    case 6: return launch_tt<BITS, NA, 6>(p, tt, grid, s);
-    case 7: return launch_tt<BITS, NA, 7>(p, tt, grid, s);
-    default: return launch_tt<BITS, NA, 8>(p, tt, grid, s);
+    case 6: return launch_tt<BITS, 6>(mp, tt, classes, grid, s);
+    case 7: return launch_tt<BITS, 7>(mp, tt, classes, grid, s);
+    default: return launch_tt<BITS, 8>(mp, tt, classes, grid, s);
   }
 }
 
-template <int BITS>
-hipError_t launch_na(const LinearParams& p, int tt, int nw, dim3 grid, hipStream_t s) {
-  if (p.n_act <= 4) return launch_nw<BITS, 4>(p, tt, nw, grid, s);
-  return launch_nw<BITS, max_pass_slots(BITS)>(p, tt, nw, grid, s);
-}
-
-hipError_t launch_reduce(const LinearParams& p, int tt, int nw, int row_groups, hipStream_t s) {
+hipError_t launch_reduce(const LaunchParams& mp, int tt, int nw, hipStream_t s) {
+  const dim3 grid(mp.rgs, tt, mp.n_groups);
   switch (nw) {
-    case 6: k_reduce_splits<6><<<dim3(row_groups, tt), 64 * 6, 0, s>>>(p); break;
-    case 7: k_reduce_splits<7><<<dim3(row_groups, tt), 64 * 7, 0, s>>>(p); break;
-    default: k_reduce_splits<8><<<dim3(row_groups, tt), 64 * 8, 0, s>>>(p); break;
+    case 6: k_reduce_splits<6><<<grid, 64 * 6, 0, s>>>(mp); break;
+    case 7: k_reduce_splits<7><<<grid, 64 * 7, 0, s>>>(mp); break;
+    default: k_reduce_splits<8><<<grid, 64 * 8, 0, s>>>(mp); break;
   }
   return hipGetLastError();
 }
@@ -921,9 +977,11 @@ constexpr int kPrefillMin = 192;
 int long_segment_tokens() { return kPrefillMin; }
 
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
-  size_t n = workspace_layout(d_in, d_out, n_linears).total;   // one 64-token group is in flight at a time
-  if (max_tokens >= kPrefillMin) n = (n + 255) / 256 * 256 + prefill_scratch_bytes(d_in, max_tokens);
-  return n;
+  const size_t per_group = workspace_layout(d_in, d_out, n_linears).total;
+  // the one-product scratch always sits behind kMaxGroups groups' worth (a workspace that has it was sized for
+  // at least kPrefillMin tokens, i.e. for all the groups)
+  if (max_tokens >= kPrefillMin) return kMaxGroups * per_group + prefill_scratch_bytes(d_in, max_tokens);
+  return groups_for(max_tokens) * per_group;
 }
 
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
@@ -932,121 +990,159 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   for (int l = 0; l < c.n_linears; ++l) d_outs[l] = c.lin[l].experts[0].d_out;
   const WorkspaceLayout wl = workspace_layout(d0.d_in, d_outs, c.n_linears);
   char* ws = reinterpret_cast<char*>(c.ws);
-  LinearParams p;
-  p.x = reinterpret_cast<const uint16_t*>(c.x);
-  p.xt = ws + wl.xt;
-  p.partial = reinterpret_cast<f32x4*>(ws + wl.partial);
+  // token groups one launch may hold: as many as the workspace has room for
+  const int max_groups = (int)(c.ws_bytes / wl.total < (size_t)kMaxGroups ? c.ws_bytes / wl.total : (size_t)kMaxGroups);
+  // what all groups of all launches have in common
+  LinearParams p0;
+  p0.x = reinterpret_cast<const uint16_t*>(c.x);
   const int pi = ceil_to(d0.d_in, kColPad);
-  p.d_in = d0.d_in;
-  p.n_linears = c.n_linears;
-  p.n_chunks = pi / kChunk;
-  p.n_sb = ceil_to(d0.k, kSalPad) / 32;
-  p.k = d0.k;
-  p.bits = d0.bits;
-  p.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
+  p0.d_in = d0.d_in;
+  p0.n_linears = c.n_linears;
+  p0.n_chunks = pi / kChunk;
+  p0.n_sb = ceil_to(d0.k, kSalPad) / 32;
+  p0.k = d0.k;
+  p0.bits = d0.bits;
+  p0.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
   const Plan pl = plan_for(d0.d_in, d_outs, c.n_linears);
   int rgs = 0;
   for (int l = 0; l < kMaxLinears; ++l) {
-    PerLinear& L = p.lin[l];
+    PerLinear& L = p0.lin[l];
     const int ll = l < c.n_linears ? l : 0;   // unused entries repeat the first (never selected)
     L.w_base = reinterpret_cast<const char*>(c.lin[ll].w_base_tiled);
     L.y = reinterpret_cast<uint16_t*>(c.lin[ll].y);
-    L.xs = reinterpret_cast<u32x4*>(ws + wl.per_linear[ll]);
     L.d_out = d_outs[ll];
     L.n_jt = ceil_to(d_outs[ll], kRowPad) / 16;
     L.rg_begin = rgs;
     if (l < c.n_linears) rgs += row_groups_of(d_outs[l], pl.nw);
     L.rg_end = rgs;
   }
-  p.nsplit = pl.nsplit;
-  for (int sp = 0; sp <= pl.nsplit; ++sp) p.c_split[sp] = (int16_t)((long)sp * p.n_chunks / pl.nsplit);
-  const dim3 grid(rgs, pl.nsplit);
+  p0.nsplit = pl.nsplit;
+  for (int sp = 0; sp <= pl.nsplit; ++sp) p0.c_split[sp] = (int16_t)((long)sp * p0.n_chunks / pl.nsplit);
+  LaunchParams mp;
+  mp.rgs = rgs;
+  mp.rg8 = (rgs + 7) / 8;
   // Token groups: up to 64 consecutive tokens that belong to at most kMaxSlots experts (the kernel sweeps the
   // chunks once per max_pass_slots of them).
   const int max_slots = kMaxSlots;
   bool first_kernel = true;   // measurement hook: the start event goes before the first streaming kernel / GEMM
-  // the streaming (decode) path over the tokens [t_lo, t_hi)
-  auto run_range = [&](int t_lo, int t_hi) -> hipError_t {
-  int e_cur = 0;   // first expert that may own token t0
-  for (int t0 = t_lo; t0 < t_hi;) {
-    while (c.seg[e_cur + 1] <= t0) ++e_cur;
-    int nt = t_hi - t0 < kTokGroup ? t_hi - t0 : kTokGroup;
-    {   // cut the group where one expert too many would start
-      int act = 0;
-      for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
-        if (c.seg[e + 1] <= c.seg[e]) continue;
-        if (++act > max_slots) { nt = c.seg[e] - t0; break; }
+  // The streaming (decode) path.  Token groups are collected from all the token ranges it covers (the stretches
+  // between long segments) and launched kMaxGroups at a time.
+  int ng = 0, tt_max = 1, items_max = 0;
+  auto flush = [&]() -> hipError_t {
+    if (ng == 0) return hipSuccess;
+    // the groups with more experts than the short variant of the kernel holds go first (stable otherwise)
+    int n_first = 0;
+    for (int g = 0; g < ng; ++g)
+      if (mp.g[g].n_act > 4) {
+        const LinearParams heavy = mp.g[g];
+        for (int h = g; h > n_first; --h) mp.g[h] = mp.g[h - 1];
+        mp.g[n_first++] = heavy;
       }
-    }
-    p.t0 = t0;
-    const int tt = nt <= 16 ? 1 : nt <= 32 ? 2 : 4;
-    // active slots: the experts that own tokens of this group, in expert order
-    int na = 0;
-    for (int tl = 0; tl < kTokGroup; ++tl) p.tok_slot[tl] = 0xff;
-    for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
-      const int lo = (c.seg[e] > t0 ? c.seg[e] : t0) - t0;
-      const int hi = (c.seg[e + 1] < t0 + nt ? c.seg[e + 1] : t0 + nt) - t0;
-      if (hi <= lo) continue;
-      for (int l = 0; l < kMaxLinears; ++l) {
-        const mes_delta& d = c.lin[l < c.n_linears ? l : 0].experts[e];
-        p.lin[l].codes[na] = reinterpret_cast<const char*>(d.codes);
-        p.lin[l].step[na] = d.step;
-        p.lin[l].sal[na] = reinterpret_cast<const char*>(d.salient);
-        p.lin[l].sidx[na] = d.salient_idx;
-      }
-      p.lo[na] = (int16_t)lo;
-      p.hi[na] = (int16_t)hi;
-      for (int tl = lo; tl < hi; ++tl) p.tok_slot[tl] = (uint8_t)na;
-      ++na;
-    }
-    for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
-      for (int l = 0; l < kMaxLinears; ++l) {
-        PerLinear& L = p.lin[l];
-        L.codes[a] = L.codes[0]; L.step[a] = L.step[0]; L.sal[a] = L.sal[0]; L.sidx[a] = L.sidx[0];
-      }
-      p.lo[a] = 0; p.hi[a] = 0;
-    }
-    // visits, tile-major: for every 16-token tile the slots that own tokens in it
-    int nv = 0;
-    for (int t = 0; t < 4; ++t)
-      for (int a = 0; a < na; ++a) {
-        const int l = p.lo[a] > 16 * t ? p.lo[a] : 16 * t;
-        const int h = p.hi[a] < 16 * t + 16 ? p.hi[a] : 16 * t + 16;
-        if (h <= l) continue;
-        p.vis_info[nv] = a | (t << 8);
-        ++nv;
-      }
-    for (int v = nv; v <= kMaxVisits; ++v) p.vis_info[v] = 0;
-    for (int t = 0; t < 4; ++t) {
-      p.tile_first[t] = 0; p.tile_last[t] = 0;
-      const int tl0 = 16 * t, tl1 = 16 * t + 15 < nt - 1 ? 16 * t + 15 : nt - 1;
-      if (tl0 < nt) { p.tile_first[t] = p.tok_slot[tl0]; p.tile_last[t] = p.tok_slot[tl1]; }
-    }
-    p.n_act = na;
-    p.n_vis = d0.k > 0 ? nv : 0;
-    p.T = t0 + nt;   // rows past the group are not this launch's: the kernels treat them as padding
-    p.tiles = (nt + 15) / 16;
-    p.n_stage_items = p.tiles * p.n_chunks;
-    p.n_items = p.n_stage_items + c.n_linears * p.n_vis;
-    k_prepare<<<p.n_items, 256, 0, s>>>(p);
+    for (int g = ng; g < kMaxGroups; ++g) mp.g[g] = mp.g[0];   // never selected
+    mp.n_groups = ng;
+    const int classes = n_first == 0 ? 0 : n_first == ng ? 1 : 2;
+    mp.n_first = n_first > 0 ? n_first : ng;
+    mp.wg_per_group = mp.rg8 * 8 * pl.nsplit;
+    k_prepare<<<dim3(items_max, ng), 256, 0, s>>>(mp);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (c.ev_start && first_kernel && (e = hipEventRecord(c.ev_start, s)) != hipSuccess) return e;
     first_kernel = false;
+    const int grid = mp.rg8 * 8 * pl.nsplit * ng;
     switch (d0.bits) {
-      case 1: e = launch_na<1>(p, tt, pl.nw, grid, s); break;
-      case 2: e = launch_na<2>(p, tt, pl.nw, grid, s); break;
-      case 4: e = launch_na<4>(p, tt, pl.nw, grid, s); break;
-      default: e = launch_na<3>(p, tt, pl.nw, grid, s); break;
+      case 1: e = launch_nw<1>(mp, tt_max, classes, pl.nw, grid, s); break;
+      case 2: e = launch_nw<2>(mp, tt_max, classes, pl.nw, grid, s); break;
+      case 4: e = launch_nw<4>(mp, tt_max, classes, pl.nw, grid, s); break;
+      default: e = launch_nw<3>(mp, tt_max, classes, pl.nw, grid, s); break;
     }
     if (e != hipSuccess) return e;
     if (c.ev_stop && (e = hipEventRecord(c.ev_stop, s)) != hipSuccess) return e;   // re-recorded by every later one
     if (pl.nsplit > 1) {
-      if ((e = launch_reduce(p, tt, pl.nw, grid.x, s)) != hipSuccess) return e;
+      if ((e = launch_reduce(mp, tt_max, pl.nw, s)) != hipSuccess) return e;
     }
-    t0 += nt;
-  }
-  return hipSuccess;
+    ng = 0; tt_max = 1; items_max = 0;
+    return hipSuccess;
+  };
+  auto run_range = [&](int t_lo, int t_hi) -> hipError_t {
+    int e_cur = 0;   // first expert that may own token t0
+    for (int t0 = t_lo; t0 < t_hi;) {
+      {
+        LinearParams& p = mp.g[ng];
+        p = p0;
+        char* wsg = ws + (size_t)ng * wl.total;
+        p.xt = wsg + wl.xt;
+        p.partial = reinterpret_cast<f32x4*>(wsg + wl.partial);
+        for (int l = 0; l < kMaxLinears; ++l) p.lin[l].xs = reinterpret_cast<u32x4*>(wsg + wl.per_linear[l < c.n_linears ? l : 0]);
+        while (c.seg[e_cur + 1] <= t0) ++e_cur;
+        int nt = t_hi - t0 < kTokGroup ? t_hi - t0 : kTokGroup;
+        {   // cut the group where one expert too many would start
+          int act = 0;
+          for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
+            if (c.seg[e + 1] <= c.seg[e]) continue;
+            if (++act > max_slots) { nt = c.seg[e] - t0; break; }
+          }
+        }
+        p.t0 = t0;
+        const int tt = nt <= 16 ? 1 : nt <= 32 ? 2 : 4;
+        // active slots: the experts that own tokens of this group, in expert order
+        int na = 0;
+        for (int tl = 0; tl < kTokGroup; ++tl) p.tok_slot[tl] = 0xff;
+        for (int e = e_cur; e < c.n_experts && c.seg[e] < t0 + nt; ++e) {
+          const int lo = (c.seg[e] > t0 ? c.seg[e] : t0) - t0;
+          const int hi = (c.seg[e + 1] < t0 + nt ? c.seg[e + 1] : t0 + nt) - t0;
+          if (hi <= lo) continue;
+          for (int l = 0; l < kMaxLinears; ++l) {
+            const mes_delta& d = c.lin[l < c.n_linears ? l : 0].experts[e];
+            p.lin[l].codes[na] = reinterpret_cast<const char*>(d.codes);
+            p.lin[l].step[na] = d.step;
+            p.lin[l].sal[na] = reinterpret_cast<const char*>(d.salient);
+            p.lin[l].sidx[na] = d.salient_idx;
+          }
+          p.lo[na] = (int16_t)lo;
+          p.hi[na] = (int16_t)hi;
+          for (int tl = lo; tl < hi; ++tl) p.tok_slot[tl] = (uint8_t)na;
+          ++na;
+        }
+        for (int a = na; a < kMaxSlots; ++a) {   // unused slots alias slot 0 so that unconditional loads stay valid
+          for (int l = 0; l < kMaxLinears; ++l) {
+            PerLinear& L = p.lin[l];
+            L.codes[a] = L.codes[0]; L.step[a] = L.step[0]; L.sal[a] = L.sal[0]; L.sidx[a] = L.sidx[0];
+          }
+          p.lo[a] = 0; p.hi[a] = 0;
+        }
+        // visits, tile-major: for every 16-token tile the slots that own tokens in it
+        int nv = 0;
+        for (int t = 0; t < 4; ++t)
+          for (int a = 0; a < na; ++a) {
+            const int l = p.lo[a] > 16 * t ? p.lo[a] : 16 * t;
+            const int h = p.hi[a] < 16 * t + 16 ? p.hi[a] : 16 * t + 16;
+            if (h <= l) continue;
+            p.vis_info[nv] = a | (t << 8);
+            ++nv;
+          }
+        for (int v = nv; v <= kMaxVisits; ++v) p.vis_info[v] = 0;
+        for (int t = 0; t < 4; ++t) {
+          p.tile_first[t] = 0; p.tile_last[t] = 0;
+          const int tl0 = 16 * t, tl1 = 16 * t + 15 < nt - 1 ? 16 * t + 15 : nt - 1;
+          if (tl0 < nt) { p.tile_first[t] = p.tok_slot[tl0]; p.tile_last[t] = p.tok_slot[tl1]; }
+        }
+        p.n_act = na;
+        p.n_vis = d0.k > 0 ? nv : 0;
+        p.T = t0 + nt;   // rows past the group are not this group's: the kernels treat them as padding
+        p.tiles = (nt + 15) / 16;
+        p.n_stage_items = p.tiles * p.n_chunks;
+        p.n_items = p.n_stage_items + c.n_linears * p.n_vis;
+        tt_max = tt > tt_max ? tt : tt_max;
+        items_max = p.n_items > items_max ? p.n_items : items_max;
+        t0 += nt;
+      }
+      ++ng;
+      if (ng == max_groups) {
+        hipError_t e = flush();
+        if (e != hipSuccess) return e;
+      }
+    }
+    return hipSuccess;
   };   // run_range
 
   // Long expert segments go to the one-product path, everything between them to the streaming path.
@@ -1054,7 +1150,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   int long_tokens = 0;
   for (int e = 0; e < c.n_experts; ++e)
     if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_tokens += c.seg[e + 1] - c.seg[e];
-  const size_t scratch_at = (wl.total + 255) / 256 * 256;
+  const size_t scratch_at = kMaxGroups * wl.total;
   const bool can_prefill = long_tokens > 0 && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, long_tokens);
   // the long segments of every linear in one go (up to 8 experts per launch), then the streaming ranges between them
   int cursor = 0;
@@ -1074,8 +1170,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
       cursor = c.seg[e + 1];
     }
   }
-  return run_range(cursor, c.T);
+  if (hipError_t err = run_range(cursor, c.T)) return err;
+  return flush();
 }
 
 }  // namespace mes
-

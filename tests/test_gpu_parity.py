@@ -363,6 +363,24 @@ def test_config4_fused_calls_at_full_size():
         torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("which,n_tokens,bits", [("q_proj", 256, 2), ("down_proj", 200, 2), ("gate_proj", 130, 3),
+                                                  ("down_proj", 256, 4), ("o_proj", 65, 1)])
+def test_config4_several_token_groups_in_one_launch(which, n_tokens, bits):
+    """65 .. 256 decode tokens at full size: one launch serves up to four 64-token groups (its workgroups share the
+    base weights through L2).  Element-wise bars against the oracle on sampled channels, and bit-for-bit the result
+    of the same call made with a workspace that only has room for one group per launch."""
+    wl = synth.config4_linear(which, device=DEV, n_tokens=n_tokens, bits=bits)
+    assert max(b - a for a, b in zip(wl.seg_offsets, wl.seg_offsets[1:])) < LONG
+    w_t = mes.mes_pack_base(wl.w_base)
+    ge = [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]
+    y = mes.mes_delta_linear(w_t, ge, wl.x, wl.seg_offsets)
+    ws1 = mes.make_workspace(wl.d_in, wl.d_out, 64, torch.device(DEV))
+    y1 = mes.mes_delta_linear(w_t, ge, wl.x, wl.seg_offsets, workspace=ws1)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y1)
+    assert sampled_rows_check(wl, y, 96, seed=7 + n_tokens, one_product=False) <= TOL
+
+
 @pytest.mark.parametrize("which", ["gate_proj", "up_proj", "down_proj"])
 @pytest.mark.parametrize("bits", [2, 3])
 def test_config3_prefill_sampled_rows(bits, which):
