@@ -674,6 +674,11 @@ def bench_step(args):
 # ------------------------------------------------------------------------------------------------ on-demand swapping
 
 def bench_swap(args):
+    """One Mistral-7B block (the seven linears, four fused calls) decoding 64-token batches whose experts come from a
+    pool: 32 experts' packed deltas in pinned host memory (one blob per expert for the whole block), 20 device slots.
+    Three variants of the same step sequence: deltas loaded on demand (a miss stalls the batch), the experts of the
+    batch four steps ahead prefetched right after the current batch is enqueued (a sequence keeps its expert and a
+    new one is known from its admission on), and every expert resident."""
     import numpy as np
     import torch
 
@@ -681,24 +686,32 @@ def bench_swap(args):
     from inputs import synth
 
     dev = "cuda:0"
-    n_experts, n_slots = 32, 16
-    d_in = d_out = 4096
+    n_experts, n_slots, ahead, max_active = 32, 20, 4, 16
     k, bits = 64 if args.k is None else args.k, args.bits
-    w = synth.normal((d_out, d_in), 0.02, 11, dev, torch.bfloat16)
-    w_t = mes.mes_pack_base(w)
-    pool = mes.ExpertPool(d_in, d_out, k, bits, mes.GRID_SYM, n_slots, n_experts, device=dev)
+    shapes = [(di, do) for _, di, do in synth.MISTRAL7B_LINEARS]
+    names = [n for n, _, _ in synth.MISTRAL7B_LINEARS]
+    w_t = [mes.mes_pack_base(synth.normal((do, di), 0.02, 11 + i, dev, torch.bfloat16)) for i, (di, do) in enumerate(shapes)]
+    pool = mes.ExpertPool([s[0] for s in shapes], [s[1] for s in shapes], [k] * 7, bits, mes.GRID_SYM, n_slots, n_experts, device=dev)
     resident = []
     for e in range(n_experts):
-        ex = synth.make_delta(d_in, d_out, k, 0.003, 15.0, 5000 + e, dev)
-        pk = mes.mes_pack_delta(ex.delta, ex.salient_idx, bits)
-        pool.register(e, pk)
-        resident.append(pk)
-    ws = mes.make_workspace(d_in, d_out, 64, torch.device(dev))
-    expert_bytes = mes.codes_bytes(d_in, d_out, bits) + 4 * d_out + mes.salient_bytes(d_out, k) + 4 * k
+        pks = []
+        for i, (di, do) in enumerate(shapes):
+            ex = synth.make_delta(di, do, k, 0.003, 15.0, 5000 + 16 * e + i, dev)
+            pks.append(mes.mes_pack_delta(ex.delta, ex.salient_idx if k else None, bits))
+            del ex
+        pool.register(e, pks)
+        resident.append(pks)
+    expert_bytes = sum(mes.codes_bytes(di, do, bits) + 4 * do + (mes.salient_bytes(do, k) + 4 * k if k else 0) for di, do in shapes)
+    index = {n: i for i, n in enumerate(names)}
+    groups = [[index[n] for n in g] for g in FUSED_GROUPS]
+    ws = torch.empty(max(mes.DeltaLinearMulti.workspace_bytes(shapes[g[0]][0], [shapes[i][1] for i in g], 64) for g in groups),
+                     dtype=torch.uint8, device=dev)
+    xs = {di: synth.normal((64, di), 1.0, 12 + di, dev, torch.bfloat16) for di in {s[0] for s in shapes}}
+    ys = [torch.empty((64, do), dtype=torch.bfloat16, device=dev) for _, do in shapes]
     # (a) what a miss costs: fill all slots from the host, timed on the compute stream (which waits for the copies)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     fills = []
-    for rep in range(5):
+    for rep in range(4):
         ids = [(rep * n_slots + i) % n_experts for i in range(n_slots)]
         before = pool.stats()[1]
         torch.cuda.synchronize()
@@ -709,44 +722,77 @@ def bench_swap(args):
         missed = pool.stats()[1] - before
         if missed:
             fills.append((missed * expert_bytes / 1e9) / (ev0.elapsed_time(ev1) * 1e-3))
-    # (b) decode steps with Zipf routing over all registered experts
+    # (b) decode steps.  A query is routed once and keeps its expert while it decodes: the batch holds 64 sequences,
+    # every step `churn` of them finish and as many new ones (experts drawn Zipf(1.1) over all registered experts)
+    # take their places.  A draw that would put more than 16 experts into one batch is repeated.
     rng = np.random.default_rng(3)
     p = 1.0 / np.arange(1, n_experts + 1) ** 1.1
     p /= p.sum()
-    x = synth.normal((64, d_in), 1.0, 12, dev, torch.bfloat16)
-    y = torch.empty((64, d_out), dtype=torch.bfloat16, device=dev)
+    churn = 2
+    seqs = list(rng.choice(n_experts, size=64, p=p))
+    while len(set(seqs)) > max_active:
+        seqs[int(rng.integers(64))] = int(rng.choice(n_experts, p=p))
     batches = []
     for _ in range(args.steps):
-        ids = np.sort(rng.choice(n_experts, size=64, p=p))
-        uniq, counts = np.unique(ids, return_counts=True)
-        uniq, counts = uniq[:n_slots], counts[:n_slots]
+        for _ in range(churn):
+            pos = int(rng.integers(64))
+            while True:
+                e = int(rng.choice(n_experts, p=p))
+                if len(set(seqs[:pos] + [e] + seqs[pos + 1:])) <= max_active:
+                    break
+            seqs[pos] = e
+        uniq, counts = np.unique(np.asarray(seqs), return_counts=True)
         batches.append((uniq.tolist(), [0] + np.cumsum(counts).tolist()))
 
-    def swap_step(i):
+    def run_calls(desc_of, seg):
+        T = seg[-1]
+        for g in groups:
+            mes.mes_delta_linear_multi_descriptors([w_t[i] for i in g], [desc_of(i) for i in g], xs[shapes[g[0]][0]][:T], seg, ws,
+                                                   [ys[i][:T] for i in g])
+
+    def swap_step(i, prefetch):
         ids, seg = batches[i % len(batches)]
         desc = pool.acquire(ids)
-        mes.mes_delta_linear_descriptors(w_t, desc, x[: seg[-1]], seg, ws, y[: seg[-1]])
+        run_calls(lambda l: desc[l], seg)
+        if prefetch:
+            # a new sequence is known when it is admitted, a few steps before it joins the decoding batch (its prompt
+            # is processed first): its expert is requested `ahead` steps early.  One expert takes about three steps'
+            # time to cross the host link.
+            pool.prefetch(batches[(i + ahead) % len(batches)][0])
+
+    res_desc = {}
 
     def resident_step(i):
         ids, seg = batches[i % len(batches)]
-        mes.mes_delta_linear(w_t, [resident[e] for e in ids], x[: seg[-1]], seg, y[: seg[-1]], ws)
+        key = i % len(batches)
+        if key not in res_desc:
+            res_desc[key] = [(mes.binding.mes_delta * len(ids))(*[resident[e][l].descriptor() for e in ids]) for l in range(7)]
+        run_calls(lambda l: res_desc[key][l], seg)
 
-    h0, m0, b0 = pool.stats()
-    regions, walls = timed_regions(swap_step, args.steps, args.warmup, args.repeats)
-    h1, m1, b1 = pool.stats()
+    results = {}
+    for name, fn in (("on_demand", lambda i: swap_step(i, False)), ("prefetch", lambda i: swap_step(i, True))):
+        h0, m0, b0 = pool.stats()
+        regions, walls = timed_regions(fn, args.steps, args.warmup, max(3, args.repeats // 2))
+        h1, m1, b1 = pool.stats()
+        n_calls = args.warmup + args.steps * len(regions)
+        results[name] = dict(ms_per_step=round(statistics.median(regions), 4), regions=[round(r, 4) for r in regions],
+                             hit_rate=round((h1 - h0) / max(h1 - h0 + m1 - m0, 1), 4),
+                             MB_copied_per_step=round((b1 - b0) / n_calls / 1e6, 3), walls=walls)
     res_regions, _ = timed_regions(resident_step, args.steps, args.warmup, max(3, args.repeats // 2))
-    ms_swap, ms_res = statistics.median(regions), statistics.median(res_regions)
-    n_calls = args.warmup + args.steps * args.repeats
-    out = base_record(args, "tokens/s, q_proj decode delta linear with on-demand swapping of the deltas from pinned host memory",
-                      round(64 / (ms_swap * 1e-3), 1), "tokens/s", ms_swap, regions, walls)
-    out["config"] = {"workload": f"swap: q_proj 4096x4096, {bits}-bit, {k} salient, {n_experts} experts in pinned host memory, {n_slots} device "
-                                 f"slots, 64-token batches routed Zipf(1.1) over all experts, LRU over requests",
+    ms_res = statistics.median(res_regions)
+    best = results["prefetch"]
+    out = base_record(args, "tokens/s, one Mistral-7B block decoding with on-demand swapping of the deltas from pinned host memory "
+                            "(next batch prefetched)", round(64 / (best["ms_per_step"] * 1e-3), 1), "tokens/s", best["ms_per_step"],
+                      best["regions"], best.pop("walls"))
+    results["on_demand"].pop("walls")
+    out["config"] = {"workload": f"swap: the 7 linears of a Mistral-7B block (4 fused calls), {bits}-bit, {k} salient, {n_experts} experts in "
+                                 f"pinned host memory (one blob per expert), {n_slots} device slots, 64 decoding sequences that keep their "
+                                 f"expert, {churn} of them replaced per step by new Zipf(1.1)-routed ones, LRU over requests, prefetch {ahead} steps ahead",
                      "tokens": 64, "expert_MB": round(expert_bytes / 1e6, 3)}
-    out["roofline"] = {"bound": "pcie", "achieved": round((b1 - b0) / n_calls / (ms_swap * 1e-3) / 1e9, 2), "peak": None, "unit": "GB/s",
-                       "frac": None, "traffic": None, "kernel": "host-to-device copies of missed experts",
+    out["roofline"] = {"bound": "pcie", "achieved": round(best["MB_copied_per_step"] / best["ms_per_step"], 2), "peak": None, "unit": "GB/s",
+                       "frac": None, "traffic": None, "kernel": "host-to-device copies of missed experts (one per expert)",
                        "fill_GBs": [round(f, 1) for f in fills]}
-    out["swap"] = {"ms_per_step_swapping": round(ms_swap, 4), "ms_per_step_all_resident": round(ms_res, 4),
-                   "hit_rate": round((h1 - h0) / max(h1 - h0 + m1 - m0, 1), 4), "MB_copied_per_step": round((b1 - b0) / n_calls / 1e6, 3)}
+    out["swap"] = {"on_demand": results["on_demand"], "prefetch": results["prefetch"], "ms_per_step_all_resident": round(ms_res, 4)}
     out["cpu_baseline"] = None
     return out
 

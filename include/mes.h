@@ -196,32 +196,64 @@ mes_status mes_delta_linear_noalloc(const void* w_base_tiled, const mes_delta* e
 
 /* ---- on-demand swapping (Section 4.1, "On-demand swapping": the base model stays on the GPU, the compressed
  * deltas of the experts a batch needs are loaded when they are needed) ----------------------------------------
- * A pool serves ONE linear layer.  It owns nothing but its bookkeeping: the caller gives it a DEVICE arena of
- * n_slots * mes_pool_slot_bytes(...) bytes (256-byte aligned; a slot holds one expert's codes, steps, salient
- * tile and salient indices) and registers up to n_experts experts whose packed buffers (exactly the buffers
- * mes_pack_delta writes, copied to the host) sit in PINNED HOST memory that stays valid and unchanged while
- * registered.  Not thread-safe: one thread drives a pool.
+ * A pool serves one linear layer (mes_pool_create) or several, up to MES_POOL_MAX_LINEARS -- e.g. the seven of a
+ * transformer block (mes_pool_create_multi: arrays d_in, d_out, k of n_linears entries; bits and grid are common).
+ * It owns nothing but its bookkeeping: the caller gives it a DEVICE arena of n_slots * slot bytes (256-byte
+ * aligned).  A slot holds one expert's packed deltas of all the pool's linears, one after the other
+ * (mes_pool_multi_slot_bytes = sum of the linears' mes_pool_slot_bytes; linear l starts mes_pool_linear_offset
+ * bytes into the slot); inside a linear's part the codes, steps, salient tile and salient indices sit at the
+ * offsets mes_pool_slot_layout reports (offsets_out[4], in that order; its return value is mes_pool_slot_bytes).
+ * Up to n_experts experts are registered, their packed data in PINNED HOST memory that stays valid and
+ * unchanged while registered:
+ *   mes_pool_register_blob: ONE host buffer of slot bytes, 16-byte aligned, laid out exactly like a slot (the
+ *     buffers mes_pack_delta writes, copied to the offsets above).  A miss is then one host-to-device copy.
+ *   mes_pool_register (single-linear pools only): the four buffers separately; a miss is four copies.
+ * Not thread-safe: one thread drives a pool, always with the same copy stream.
  *
- * mes_pool_acquire(pool, experts[n], ...): makes the n distinct experts resident and writes their descriptors
- * to out[n] (HOST array), in the order asked.  An expert already in a slot is a hit.  A miss overwrites the
- * least recently acquired slot that holds none of this request's experts (never-used slots first, lowest slot
- * index among equals) with asynchronous host-to-device copies on `copy_stream`; these copies start only
- * after everything enqueued on `compute_stream` so far (a kernel may still read the slot), and
- * `compute_stream` is made to wait for them, so work enqueued on it after the call sees the new contents.
- * Descriptors of EARLIER acquires are stale once a later acquire has missed.  n > n_slots is MES_ERR_SHAPE.
+ * mes_pool_acquire_multi(pool, experts[n], out, ...): makes the n distinct experts resident and writes their
+ * descriptors to out (HOST array [n_linears][n]: linear-major, within a linear in the order asked).  An expert
+ * already in a slot is a hit.  A miss overwrites the least recently used slot that holds none of this request's
+ * experts (never-used slots first, lowest slot index among equals; "used" = handed out by an acquire or filled
+ * by a prefetch) with asynchronous copies on `copy_stream`; these copies start only after everything enqueued on
+ * `compute_stream` so far (a kernel may still read the slot), and `compute_stream` is made to wait for them --
+ * and for any prefetch into a slot it hands out -- so work enqueued on it after the call sees the new contents.
+ * The descriptors are valid until the next acquire.  n > n_slots is MES_ERR_SHAPE.  If a copy cannot be issued
+ * the call fails with MES_ERR_DEVICE and nothing it loaded counts as resident.
+ * mes_pool_acquire: the same for a single-linear pool (out[n]).
+ *
+ * mes_pool_prefetch(pool, experts[n], n_loaded, copy_stream): starts loading those of the n experts that are not
+ * resident, WITHOUT making any stream wait for the copies: a later acquire of them is a hit (and does the
+ * waiting).  Only slots the latest acquire did not hand out, and no prefetch since has filled, are overwritten,
+ * least recently used first; the copies start after the compute stream's position at that latest acquire, i.e.
+ * they run under the kernels of the current batch.  Experts for which no such slot is left are skipped (they
+ * will be misses of their acquire); *n_loaded (may be NULL) = how many copies were started.
+ *
  * A pool created with dry_run != 0 does the bookkeeping only (no GPU call): for tests of the policy.
- * mes_pool_stats: hits, misses and bytes copied since creation (any pointer may be NULL). */
+ * mes_pool_stats: hits and misses of the acquires, and payload bytes copied (prefetches included) since
+ * creation (any pointer may be NULL); mes_pool_prefetched: experts loaded by prefetches. */
+#define MES_POOL_MAX_LINEARS 8
 typedef struct mes_pool mes_pool;
 size_t mes_pool_slot_bytes(int d_in, int d_out, int k, int bits);
+size_t mes_pool_slot_layout(int d_in, int d_out, int k, int bits, size_t offsets_out[4]);
+size_t mes_pool_multi_slot_bytes(int n_linears, const int32_t* d_in, const int32_t* d_out, const int32_t* k, int bits);
 mes_status mes_pool_create(int d_in, int d_out, int k, int bits, int grid, int n_slots, int n_experts, void* arena,
                            size_t arena_bytes, int dry_run, mes_pool** out);
+mes_status mes_pool_create_multi(int n_linears, const int32_t* d_in, const int32_t* d_out, const int32_t* k, int bits,
+                                 int grid, int n_slots, int n_experts, void* arena, size_t arena_bytes, int dry_run,
+                                 mes_pool** out);
 void mes_pool_destroy(mes_pool* pool);
+size_t mes_pool_linear_offset(const mes_pool* pool, int linear);
 mes_status mes_pool_register(mes_pool* pool, int expert, const void* codes, const float* step, const void* salient,
                              const int32_t* salient_idx);
+mes_status mes_pool_register_blob(mes_pool* pool, int expert, const void* host_blob);
 mes_status mes_pool_acquire(mes_pool* pool, const int32_t* experts, int n, mes_delta* out, void* copy_stream,
                             void* compute_stream);
+mes_status mes_pool_acquire_multi(mes_pool* pool, const int32_t* experts, int n, mes_delta* out, void* copy_stream,
+                                  void* compute_stream);
+mes_status mes_pool_prefetch(mes_pool* pool, const int32_t* experts, int n, int* n_loaded, void* copy_stream);
 int mes_pool_slot_of(const mes_pool* pool, int expert);   /* slot the expert is resident in, or -1 */
 mes_status mes_pool_stats(const mes_pool* pool, uint64_t* hits, uint64_t* misses, uint64_t* bytes_copied);
+uint64_t mes_pool_prefetched(const mes_pool* pool);
 
 /* ---- learning the step sizes (Section 4.1, "Efficient distillation", taken layer by layer; straight-through
  * estimator of Section 3 for Eq. 1).  Offline. -----------------------------------------------------------------

@@ -30,6 +30,8 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_delta_linear", "mes_linear_multi_workspace_bytes",
            "mes_delta_linear_multi", "mes_time_next_call", "mes_copy_probe", "mes_pool_slot_bytes", "mes_pool_create",
            "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
+           "mes_pool_slot_layout", "mes_pool_multi_slot_bytes", "mes_pool_create_multi", "mes_pool_linear_offset",
+           "mes_pool_register_blob", "mes_pool_acquire_multi", "mes_pool_prefetch", "mes_pool_prefetched",
            "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_noalloc_scratch_bytes",
            "mes_delta_linear_noalloc", "mes_long_segment_tokens"]
 
@@ -120,6 +122,23 @@ def _load() -> ctypes.CDLL:
     lib.mes_pool_acquire.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), c_int, ctypes.POINTER(mes_delta), vp, vp]
     lib.mes_pool_slot_of.restype = c_int
     lib.mes_pool_slot_of.argtypes = [vp, c_int]
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.mes_pool_slot_layout.restype = c_sz
+    lib.mes_pool_slot_layout.argtypes = [c_int, c_int, c_int, c_int, ctypes.POINTER(c_sz)]
+    lib.mes_pool_multi_slot_bytes.restype = c_sz
+    lib.mes_pool_multi_slot_bytes.argtypes = [c_int, i32p, i32p, i32p, c_int]
+    lib.mes_pool_create_multi.restype = c_int
+    lib.mes_pool_create_multi.argtypes = [c_int, i32p, i32p, i32p, c_int, c_int, c_int, c_int, vp, c_sz, c_int, ctypes.POINTER(vp)]
+    lib.mes_pool_linear_offset.restype = c_sz
+    lib.mes_pool_linear_offset.argtypes = [vp, c_int]
+    lib.mes_pool_register_blob.restype = c_int
+    lib.mes_pool_register_blob.argtypes = [vp, c_int, vp]
+    lib.mes_pool_acquire_multi.restype = c_int
+    lib.mes_pool_acquire_multi.argtypes = [vp, i32p, c_int, ctypes.POINTER(mes_delta), vp, vp]
+    lib.mes_pool_prefetch.restype = c_int
+    lib.mes_pool_prefetch.argtypes = [vp, i32p, c_int, ctypes.POINTER(c_int), vp]
+    lib.mes_pool_prefetched.restype = ctypes.c_uint64
+    lib.mes_pool_prefetched.argtypes = [vp]
     lib.mes_pool_stats.restype = c_int
     lib.mes_pool_stats.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]
     return lib
@@ -318,6 +337,20 @@ def mes_delta_linear_descriptors(w_base_tiled: torch.Tensor, desc, x: torch.Tens
     return y
 
 
+def mes_delta_linear_multi_descriptors(ws_tiled: Sequence[torch.Tensor], descs: Sequence, x: torch.Tensor,
+                                       seg_offsets: Sequence[int], workspace: torch.Tensor,
+                                       ys: Optional[Sequence[torch.Tensor]] = None):
+    """mes_delta_linear_multi on ready ctypes arrays of mes_delta, one per layer (e.g. what a layer-spanning
+    ExpertPool.acquire returns)."""
+    n, E, T = len(descs), len(descs[0]), x.shape[0]
+    if ys is None:
+        ys = [torch.empty((T, d[0].d_out), dtype=torch.bfloat16, device=x.device) for d in descs]
+    lin = (mes_linear * n)(*[mes_linear(ws_tiled[l].data_ptr(), descs[l], ys[l].data_ptr()) for l in range(n)])
+    seg = (ctypes.c_int32 * (E + 1))(*seg_offsets)
+    _check(lib.mes_delta_linear_multi(lin, n, E, _ptr(x), T, seg, _ptr(workspace), workspace.numel(), _stream(x.device)))
+    return list(ys)
+
+
 class DeltaLinearMulti:
     """Marshalled arguments of mes_delta_linear_multi: several layers that read the same activations and routing."""
 
@@ -358,14 +391,21 @@ class DeltaLinearMulti:
 
 
 class ExpertPool:
-    """On-demand swapping for one linear layer (mes_pool_* in mes.h): a device arena of `n_slots` slots and
-    pinned host copies of every registered expert's packed buffers."""
+    """On-demand swapping (mes_pool_* in mes.h): a device arena of `n_slots` slots and one pinned host blob per
+    registered expert.  d_in, d_out, k: ints for a pool over one linear layer, or equally long sequences for a pool
+    whose slots hold an expert's deltas of several layers (a miss is one copy either way)."""
 
-    def __init__(self, d_in: int, d_out: int, k: int, bits: int, grid: int, n_slots: int, n_experts: int,
+    def __init__(self, d_in, d_out, k, bits: int, grid: int, n_slots: int, n_experts: int,
                  device="cuda:0", dry_run: bool = False):
-        self.d_in, self.d_out, self.k, self.bits, self.grid = d_in, d_out, k, bits, grid
+        self.single = isinstance(d_in, int)
+        as_list = lambda v: [int(v)] if isinstance(v, int) else [int(a) for a in v]
+        self.d_in, self.d_out, self.k = as_list(d_in), as_list(d_out), as_list(k)
+        self.n_linears = len(self.d_in)
+        assert len(self.d_out) == self.n_linears and len(self.k) == self.n_linears
+        self.bits, self.grid = bits, grid
         self.n_slots = n_slots
-        self.slot_bytes = lib.mes_pool_slot_bytes(d_in, d_out, k, bits)
+        arr = lambda v: (ctypes.c_int32 * self.n_linears)(*v)
+        self.slot_bytes = lib.mes_pool_multi_slot_bytes(self.n_linears, arr(self.d_in), arr(self.d_out), arr(self.k), bits)
         if dry_run:
             self.arena, arena_ptr = None, 256          # any aligned non-null address: a dry-run pool never touches it
         else:
@@ -374,39 +414,67 @@ class ExpertPool:
             self.copy_stream = torch.cuda.Stream(device=device)
         self.device = device
         self.dry_run = dry_run
-        self.host = {}                                  # expert -> pinned host tensors (kept alive here)
+        self.host = {}                                  # expert -> pinned host blob (kept alive here)
         h = ctypes.c_void_p()
-        _check(lib.mes_pool_create(d_in, d_out, k, bits, grid, n_slots, n_experts, arena_ptr,
-                                   self.slot_bytes * n_slots, int(dry_run), ctypes.byref(h)))
+        _check(lib.mes_pool_create_multi(self.n_linears, arr(self.d_in), arr(self.d_out), arr(self.k), bits, grid, n_slots,
+                                         n_experts, arena_ptr, self.slot_bytes * n_slots, int(dry_run), ctypes.byref(h)))
         self.handle = h
+        # where each linear's buffers sit inside a slot / blob
+        self.offsets = []
+        for l in range(self.n_linears):
+            off = (ctypes.c_size_t * 4)()
+            lib.mes_pool_slot_layout(self.d_in[l], self.d_out[l], self.k[l], bits, off)
+            base = lib.mes_pool_linear_offset(self.handle, l)
+            self.offsets.append([base + int(o) for o in off])
 
-    def register(self, expert: int, packed: "PackedDelta") -> None:
-        """Copies the packed buffers to pinned host memory and registers them."""
-        def pin(t):
-            if t is None:
-                return None
-            out = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
-            out.copy_(t)
-            return out
-        bufs = (pin(packed.codes), pin(packed.step), pin(packed.salient), pin(packed.salient_idx))
-        self.host[expert] = bufs
-        _check(lib.mes_pool_register(self.handle, expert, *[None if b is None else b.data_ptr() for b in bufs]))
+    def register(self, expert: int, packed) -> None:
+        """packed: a PackedDelta (single-linear pool) or one per linear.  Builds the expert's blob in pinned host
+        memory and registers it."""
+        packed = [packed] if self.single and not isinstance(packed, (list, tuple)) else list(packed)
+        assert len(packed) == self.n_linears
+        blob = torch.zeros(self.slot_bytes, dtype=torch.uint8, pin_memory=True)
+        for l, pk in enumerate(packed):
+            for off, t in zip(self.offsets[l], (pk.codes, pk.step, pk.salient, pk.salient_idx)):
+                if t is None or t.numel() == 0:
+                    continue
+                raw = t.contiguous().view(torch.uint8).reshape(-1)
+                blob[off: off + raw.numel()].copy_(raw)
+        if expert in self.host and not self.dry_run:
+            # a copy out of the blob this one replaces may still be in flight
+            self.copy_stream.synchronize()
+        _check(lib.mes_pool_register_blob(self.handle, expert, blob.data_ptr()))
+        self.host[expert] = blob
 
     def register_raw(self, expert: int, codes: int, step: int, salient: int, sidx: int) -> None:
         _check(lib.mes_pool_register(self.handle, expert, codes, step, salient, sidx))
 
+    def _streams(self):
+        if self.dry_run:
+            return None, None
+        return self.copy_stream.cuda_stream, _stream(torch.device(self.device))
+
     def acquire(self, experts: Sequence[int]):
-        """Makes `experts` resident; returns the ctypes array of their descriptors (valid until the next miss)."""
+        """Makes `experts` resident; returns the ctypes array of their descriptors (valid until the next acquire):
+        [n] for a single-linear pool, else a list with one such array per linear."""
         n = len(experts)
         ids = (ctypes.c_int32 * n)(*experts)
-        out = (mes_delta * n)()
-        if self.dry_run:
-            cs = ks = None
-        else:
-            cs = self.copy_stream.cuda_stream
-            ks = _stream(torch.device(self.device))
-        _check(lib.mes_pool_acquire(self.handle, ids, n, out, cs, ks))
-        return out
+        out = (mes_delta * (n * self.n_linears))()
+        cs, ks = self._streams()
+        _check(lib.mes_pool_acquire_multi(self.handle, ids, n, out, cs, ks))
+        if self.single:
+            return out
+        size = ctypes.sizeof(mes_delta) * n
+        return [(mes_delta * n).from_buffer(out, l * size) for l in range(self.n_linears)]   # views: `out` stays alive with them
+
+    def prefetch(self, experts: Sequence[int]) -> int:
+        """Starts loading the experts that are not resident into slots the latest acquire did not hand out; returns
+        how many copies were started."""
+        n = len(experts)
+        ids = (ctypes.c_int32 * n)(*experts)
+        loaded = ctypes.c_int(0)
+        cs, _ = self._streams()
+        _check(lib.mes_pool_prefetch(self.handle, ids, n, ctypes.byref(loaded), cs))
+        return loaded.value
 
     def slot_of(self, expert: int) -> int:
         return lib.mes_pool_slot_of(self.handle, expert)
@@ -415,6 +483,9 @@ class ExpertPool:
         h, m, b = ctypes.c_uint64(), ctypes.c_uint64(), ctypes.c_uint64()
         _check(lib.mes_pool_stats(self.handle, ctypes.byref(h), ctypes.byref(m), ctypes.byref(b)))
         return h.value, m.value, b.value
+
+    def prefetched(self) -> int:
+        return lib.mes_pool_prefetched(self.handle)
 
     def __del__(self):
         if getattr(self, "handle", None):

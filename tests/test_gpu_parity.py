@@ -449,6 +449,51 @@ def test_on_demand_swapping_gives_the_resident_result():
     assert nbytes == misses * (mes.codes_bytes(d_in, d_out, bits) + 4 * d_out + mes.salient_bytes(d_out, k) + 4 * k)
 
 
+def test_layer_spanning_pool_with_prefetch_gives_the_resident_result():
+    """A pool whose slots hold an expert's deltas of three linear layers (two of them read the same activations and go
+    through one fused call), one pinned blob and one copy per expert.  After every acquire the next batch's experts
+    are prefetched -- those copies run under the current batch's kernels and may only go to slots the current batch
+    does not use.  Every batch must give, bit for bit, what the always-resident packed deltas give; residency and
+    counters must follow the policy oracle."""
+    from oracle.pool_oracle import LruPool
+    shapes = [(520, 136, 16), (520, 72, 16), (264, 200, 8)]            # (d_in, d_out, k)
+    bits, n_experts, n_slots = 2, 18, 8
+    wls = [synth.small_case(di, do, [0] + [e + 1 for e in range(n_experts)], k, bits, seed=70 + i) for i, (di, do, k) in enumerate(shapes)]
+    w_t = [mes.mes_pack_base(wl.w_base.to(DEV)) for wl in wls]
+    ge = [gpu_experts(wl) for wl in wls]
+    pool = mes.ExpertPool([s[0] for s in shapes], [s[1] for s in shapes], [s[2] for s in shapes], bits, 0, n_slots, n_experts, device=DEV)
+    for e in range(n_experts):
+        pool.register(e, [ge[l][e] for l in range(3)])
+    ws_a = torch.empty(mes.DeltaLinearMulti.workspace_bytes(520, [136, 72], 64), dtype=torch.uint8, device=DEV)
+    ws_b = mes.make_workspace(264, 200, 64, torch.device(DEV))
+    ref = LruPool(n_slots)
+    rng = np.random.default_rng(9)
+    batches = []
+    for step in range(14):
+        ids = sorted(rng.choice(n_experts, size=int(rng.integers(1, 5)), replace=False).tolist())
+        batches.append((ids, [0] + np.cumsum(rng.integers(1, 12, size=len(ids))).tolist()))
+    for step, (ids, seg) in enumerate(batches):
+        xa = synth.normal((seg[-1], 520), 1.0, 800 + step, DEV, torch.bfloat16)
+        xb = synth.normal((seg[-1], 264), 1.0, 900 + step, DEV, torch.bfloat16)
+        ref.acquire(ids)
+        desc = pool.acquire(ids)
+        ya = mes.mes_delta_linear_multi_descriptors(w_t[:2], desc[:2], xa, seg, ws_a)
+        yb = mes.mes_delta_linear_descriptors(w_t[2], desc[2], xb, seg, ws_b)
+        if step + 1 < len(batches):
+            assert pool.prefetch(batches[step + 1][0]) == len(ref.prefetch(batches[step + 1][0]))
+        # the same calls on the resident deltas (the fused one included: its column split differs from a single call's)
+        res = mes.DeltaLinearMulti([(w_t[l], [ge[l][e] for e in ids]) for l in range(2)], 64)(xa, seg)
+        res.append(mes.mes_delta_linear(w_t[2], [ge[2][e] for e in ids], xb, seg))
+        torch.cuda.synchronize()
+        for l, y in enumerate(ya + [yb]):
+            assert torch.equal(y.view(torch.int16), res[l].view(torch.int16)), f"batch {step}, layer {l}"
+        for e in range(n_experts):
+            assert pool.slot_of(e) == ref.slot_of(e)
+    hits, misses, _ = pool.stats()
+    assert (hits, misses, pool.prefetched()) == (ref.hits, ref.misses, ref.prefetched)
+    assert pool.prefetched() > n_slots and misses < pool.prefetched()       # slots recycled by prefetches; most loads were ahead of need
+
+
 @pytest.mark.parametrize("d_in,d_out,seg,k,bits,grid", [
     (520, 136, [0, 5, 305, 310, 330, 560], 16, 2, 0),     # long segments (300 and 230 tokens) between short ones
     (1032, 72, [0, 200], 33, 3, 1),                        # one long segment only, Eq. 1 grid, 3 bits

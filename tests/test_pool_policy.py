@@ -59,6 +59,32 @@ def test_lru_inclusion_property():
     assert misses == sorted(misses, reverse=True) and misses[-1] == len(set(seq))
 
 
+def test_prefetch_spares_the_slots_of_the_latest_acquire():
+    p = LruPool(4)
+    p.acquire([0, 1])                                   # slots 0, 1; two slots free
+    assert p.prefetch([2, 3, 4]) == [2, 3]              # the free slots go; nothing else may: 4 is skipped
+    assert p.slot_of(0) >= 0 and p.slot_of(1) >= 0 and p.slot_of(4) == -1
+    slots, loaded = p.acquire([2, 3])                   # both prefetched: hits
+    assert loaded == [] and p.hits == 2 and p.misses == 2
+    assert p.prefetch([4]) == [4] and p.slot_of(0) == -1     # 0 and 1 are older than the latest acquire now: 0 is the oldest
+    assert p.prefetch([5]) == [5] and p.slot_of(1) == -1
+    assert p.prefetch([6]) == []                             # 2, 3 belong to the latest acquire, 4, 5 were just prefetched
+    assert p.prefetched == 4
+
+
+def test_prefetch_of_the_next_request_turns_its_misses_into_hits():
+    """With twice as many slots as a request needs, prefetching request i + 1 right after acquiring request i
+    leaves the acquires nothing to load but the very first request."""
+    rng = random.Random(3)
+    p = LruPool(8)
+    reqs = [rng.sample(range(30), 4) for _ in range(100)]
+    for i, r in enumerate(reqs):
+        p.acquire(r)
+        if i + 1 < len(reqs):
+            p.prefetch(reqs[i + 1])
+    assert p.misses == 4
+
+
 # ---------------------------------------------------------------- the library's bookkeeping against the oracle
 
 @needs_lib
@@ -92,6 +118,45 @@ def test_dry_run_pool_follows_the_oracle(n_slots, n_experts, seed):
 
 
 @needs_lib
+@pytest.mark.parametrize("n_slots,n_experts,seed", [(6, 20, 0), (16, 40, 1), (2, 7, 2)])
+def test_dry_run_pool_with_prefetches_follows_the_oracle(n_slots, n_experts, seed):
+    """A pool over three linear layers, acquires and prefetches interleaved at random: residency, slots, counters and
+    the descriptors' addresses against the oracle and the documented slot layout."""
+    d_in, d_out, k, bits = [264, 264, 520], [72, 136, 264], [5, 0, 16], 2
+    pool = mes.ExpertPool(d_in, d_out, k, bits, 0, n_slots, n_experts, dry_run=True)
+    for e in range(n_experts):
+        B._check(B.lib.mes_pool_register_blob(pool.handle, e, 4096 + e * 16))   # fake pinned address: never dereferenced
+    up = lambda v: (v + 255) // 256 * 256
+    lin_bytes = [B.lib.mes_pool_slot_bytes(d_in[l], d_out[l], k[l], bits) for l in range(3)]
+    assert pool.slot_bytes == sum(lin_bytes)
+    assert [B.lib.mes_pool_linear_offset(pool.handle, l) for l in range(3)] == [0, lin_bytes[0], lin_bytes[0] + lin_bytes[1]]
+    payload = sum(B.codes_bytes(d_in[l], d_out[l], bits) + 4 * d_out[l] + (B.salient_bytes(d_out[l], k[l]) + 4 * k[l] if k[l] else 0)
+                  for l in range(3))
+    ref = LruPool(n_slots)
+    rng = random.Random(seed)
+    copied = 0
+    for _ in range(400):
+        req = rng.sample(range(n_experts), rng.randint(1, n_slots))
+        if rng.random() < 0.4:
+            loaded = ref.prefetch(req)
+            assert pool.prefetch(req) == len(loaded)
+        else:
+            slots, loaded = ref.acquire(req)
+            desc = pool.acquire(req)
+            for l in range(3):
+                for i, e in enumerate(req):
+                    base = 256 + slots[i] * pool.slot_bytes + sum(lin_bytes[:l])
+                    d = desc[l][i]
+                    assert d.codes == base and d.step == base + up(B.codes_bytes(d_in[l], d_out[l], bits))
+                    assert (d.d_in, d.d_out, d.k, d.bits) == (d_in[l], d_out[l], k[l], bits)
+                    assert (d.salient is None) == (k[l] == 0)
+        copied += len(loaded) * payload
+        for e in range(n_experts):
+            assert pool.slot_of(e) == ref.slot_of(e)
+    assert pool.stats() == (ref.hits, ref.misses, copied) and pool.prefetched() == ref.prefetched
+
+
+@needs_lib
 def test_pool_argument_errors():
     lib = B.lib
     h = ctypes.c_void_p()
@@ -116,5 +181,19 @@ def test_pool_argument_errors():
     assert lib.mes_pool_acquire(pool, ids, 2, out, None, None) == 1          # expert 1 was never registered
     assert lib.mes_pool_acquire(pool, ids, 1, out, None, None) == 0
     assert lib.mes_pool_slot_of(pool, 0) == 0 and lib.mes_pool_slot_of(pool, 1) == -1
+    assert lib.mes_pool_prefetch(pool, ids, 2, None, None) == 1              # expert 1 was never registered
+    assert lib.mes_pool_prefetch(pool, ids, 1, None, None) == 0
+    assert lib.mes_pool_register_blob(pool, 1, None) == 1 and lib.mes_pool_register_blob(pool, 1, 264) == 6
+    assert lib.mes_pool_register_blob(pool, 1, 512) == 0
     lib.mes_pool_destroy(pool)
     assert lib.mes_pool_slot_bytes(256, 256, 8, 5) == 0
+    three = (ctypes.c_int32 * 3)(256, 256, 256)
+    ks = (ctypes.c_int32 * 3)(8, 0, 300)
+    assert lib.mes_pool_create_multi(3, three, three, ks, 2, 0, 4, 8, 256, 1 << 30, 1, ctypes.byref(h)) == 4
+    assert lib.mes_pool_create_multi(9, three, three, ks, 2, 0, 4, 8, 256, 1 << 30, 1, ctypes.byref(h)) == 2
+    ks[2] = 16
+    assert lib.mes_pool_create_multi(3, three, three, ks, 2, 0, 4, 8, 256, 1 << 30, 1, ctypes.byref(h)) == 0
+    multi = ctypes.c_void_p(h.value)
+    assert lib.mes_pool_register(multi, 0, 256, 256, 256, 256) == 2          # four-buffer registration is for single-linear pools
+    assert lib.mes_pool_acquire(multi, ids, 1, out, None, None) == 2
+    lib.mes_pool_destroy(multi)
