@@ -186,6 +186,9 @@ def main():
     ap.add_argument("--sample-frac", type=int, default=0, help="oracle leg: 1/N of the output channels (default 2 for c4)")
     ap.add_argument("--breakdown", action="store_true", help="also report every call's kernel time (stderr and JSON)")
     ap.add_argument("--unfused", action="store_true", help="c4: seven single-layer calls per step instead of four")
+    ap.add_argument("--mlp-act", default="none", choices=["none", "fused", "separate"],
+                    help="c4: also form h = SiLU(gate) * up, inside the gate+up call (mes_delta_linear_gated) or by a separate "
+                         "elementwise kernel after it (no oracle leg in these modes)")
     ap.add_argument("--graph", action="store_true",
                     help="c4: capture one step as a HIP graph and replay it in the timed region (outputs checked against eager)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -275,14 +278,27 @@ def bench_decode(args):
         if len(Ls) == 1:
             L = Ls[0]
             calls.append(dict(name=L["name"], bytes=L["bytes"], ys=[L["y"]], run=(lambda L=L: L["lin"](L["x"], L["seg"], L["y"]))))
+        elif args.mlp_act == "fused" and [L["name"] for L in Ls] == ["gate_proj", "up_proj"]:
+            g_, u_ = Ls
+            gated = mes.DeltaLinearGated(g_["lin"].w, g_["lin"].experts, u_["lin"].w, u_["lin"].experts, T)
+            h = torch.empty((T, g_["d_out"]), dtype=torch.bfloat16, device=dev)
+            nbytes = g_["bytes"] + u_["bytes"] - 2 * T * g_["d_in"] - 2 * T * g_["d_out"]   # x read once, one output
+            calls.append(dict(name="SiLU(gate_proj)*up_proj", bytes=nbytes, ys=[h],
+                              run=(lambda gated=gated, L0=g_, h=h: gated(L0["x"], L0["seg"], h))))
         else:
             assert all(torch.equal(L["x"], Ls[0]["x"]) and L["seg"] == Ls[0]["seg"] for L in Ls), \
                 "fused layers must read the same activations and routing"
             fused = mes.DeltaLinearMulti([(L["lin"].w, L["lin"].experts) for L in Ls], T)
             ys = [L["y"] for L in Ls]
             nbytes = sum(L["bytes"] for L in Ls) - (len(Ls) - 1) * 2 * T * Ls[0]["d_in"]   # the shared activations are read once
-            calls.append(dict(name="+".join(L["name"] for L in Ls), bytes=nbytes, ys=ys,
-                              run=(lambda fused=fused, L0=Ls[0], ys=ys: fused(L0["x"], L0["seg"], ys))))
+            run = (lambda fused=fused, L0=Ls[0], ys=ys: fused(L0["x"], L0["seg"], ys))
+            if args.mlp_act == "separate" and [L["name"] for L in Ls] == ["gate_proj", "up_proj"]:
+                h = torch.empty_like(ys[0])
+
+                def run(fused=fused, L0=Ls[0], ys=ys, h=h):
+                    fused(L0["x"], L0["seg"], ys)
+                    torch.mul(torch.nn.functional.silu(ys[0]), ys[1], out=h)
+            calls.append(dict(name="+".join(L["name"] for L in Ls), bytes=nbytes, ys=ys, run=run))
     calls_per_step = len(calls) if c4 else 1
 
     def one_step(i):
@@ -367,7 +383,7 @@ def bench_decode(args):
         del src, dst
 
     cpu_baseline = parity = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.mlp_act == "none":
         one_step(0)
         torch.cuda.synchronize()
         t_cpu, covered, parity = sampler.run([L["y"] for L in layers])
@@ -385,7 +401,7 @@ def bench_decode(args):
                      f"{args.bits}-bit codes ({args.grid} grid), {k} fp16 salient channels") if c4 else
                     f"c2: Mistral-7B q_proj 4096x4096, 3 experts, 48 decode tokens 16/16/16, 2-bit, 64 salient; {copies} rotating copies",
         "tokens": T, "experts": 16 if c4 else 3, "bits": args.bits, "calls_per_step": calls_per_step,
-        "graph_replay": bool(args.graph), "fused_calls": [c["name"] for c in calls] if c4 else None,
+        "graph_replay": bool(args.graph), "mlp_act": args.mlp_act, "fused_calls": [c["name"] for c in calls] if c4 else None,
         "active_experts": layers[0]["n_active"]}
     out["roofline"] = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "kernel": "k_delta_linear",

@@ -194,6 +194,22 @@ size_t mes_noalloc_scratch_bytes(void);
 mes_status mes_delta_linear_noalloc(const void* w_base_tiled, const mes_delta* experts, int n_experts,
                                     const void* x, int T, const int32_t* seg_offsets, void* y, void* stream);
 
+/* ---- gated MLP input: h = SiLU(y_gate) * y_up, element by element --------------------------------------------
+ * The models the method is evaluated on (Section 5: Mistral-7B, LLaMA-2-13B) use a gated MLP: its down projection
+ * reads SiLU(gate_proj(x)) * up_proj(x), SiLU(v) = v / (1 + exp(-v)).  y_gate and y_up are two mes_delta_linear
+ * results (Eq. 4) over the same x and routing; this call computes both in one pass (like mes_delta_linear_multi)
+ * and writes only h: bf16 [T, d_out], DEVICE, 16-byte aligned, rows in the order of x.  y_gate and y_up are NOT
+ * rounded to bf16 on the way: SiLU and the product are taken in fp32 on the fp32 sums, h is rounded once.
+ * The two layers must agree in d_in, d_out, k, bits and grid; each has its own base, experts and salient sets.
+ * All tokens take the streaming path (there is no long-segment route here).  Arguments otherwise as for
+ * mes_delta_linear; workspace >= mes_gated_workspace_bytes(d_in, d_out, max_tokens) (max_tokens as for
+ * mes_linear_workspace_bytes: <= 64, <= 128 or more decide how many 64-token groups one launch may hold). */
+size_t mes_gated_workspace_bytes(int d_in, int d_out, int max_tokens);
+mes_status mes_delta_linear_gated(const void* w_gate_tiled, const mes_delta* gate_experts, const void* w_up_tiled,
+                                  const mes_delta* up_experts, int n_experts, const void* x, int T,
+                                  const int32_t* seg_offsets, void* h, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
 /* ---- on-demand swapping (Section 4.1, "On-demand swapping": the base model stays on the GPU, the compressed
  * deltas of the experts a batch needs are loaded when they are needed) ----------------------------------------
  * A pool serves one linear layer (mes_pool_create) or several, up to MES_POOL_MAX_LINEARS -- e.g. the seven of a

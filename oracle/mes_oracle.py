@@ -180,6 +180,23 @@ def delta_linear(x64: np.ndarray, w_base64: np.ndarray, experts, seg_offsets) ->
 
 
 # ------------------------------------------------------------------------------------------------
+# The gated MLP input of the evaluated models (Section 5: Mistral-7B, LLaMA-2-13B)
+# ------------------------------------------------------------------------------------------------
+
+def silu(v: np.ndarray) -> np.ndarray:
+    """SiLU(v) = v / (1 + exp(-v)), fp64, written so that large negative v does not overflow."""
+    v = np.asarray(v, dtype=np.float64)
+    e = np.exp(-np.abs(v))
+    return np.where(v >= 0, v / (1.0 + e), v * e / (1.0 + e))
+
+
+def gated_mlp_input(x64, w_gate64, gate_experts, w_up64, up_experts, seg_offsets) -> np.ndarray:
+    """h = SiLU(y_gate) * y_up with y_gate, y_up two Eq. 4 layers over the same rows and routing -- what the down
+    projection of a gated MLP block reads.  Nothing is rounded on the way (fp64 throughout)."""
+    return silu(delta_linear(x64, w_gate64, gate_experts, seg_offsets)) * delta_linear(x64, w_up64, up_experts, seg_offsets)
+
+
+# ------------------------------------------------------------------------------------------------
 # Eq. 2: salient input-channel selection
 # ------------------------------------------------------------------------------------------------
 

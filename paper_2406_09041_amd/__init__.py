@@ -8,5 +8,5 @@ from .binding import (  # noqa: F401
     base_bytes, codes_bytes, linear_workspace_bytes, make_workspace, mes_delta_linear, mes_pack_base,
     mes_pack_delta, mes_select_salient, mes_unpack_base, mes_unpack_delta, salient_bytes, DeltaLinearMulti, KernelTimer,
     mes_copy_probe, ExpertPool, mes_delta_linear_descriptors, mes_delta_linear_multi_descriptors, StepGrad, mes_step_adamw,
-    mes_delta_linear_noalloc,
+    mes_delta_linear_noalloc, DeltaLinearGated,
 )

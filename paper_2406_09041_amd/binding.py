@@ -32,6 +32,7 @@ EXPORTS = ["mes_base_bytes", "mes_codes_bytes", "mes_salient_bytes", "mes_pack_w
            "mes_pool_destroy", "mes_pool_register", "mes_pool_acquire", "mes_pool_slot_of", "mes_pool_stats",
            "mes_pool_slot_layout", "mes_pool_multi_slot_bytes", "mes_pool_create_multi", "mes_pool_linear_offset",
            "mes_pool_register_blob", "mes_pool_acquire_multi", "mes_pool_prefetch", "mes_pool_prefetched",
+           "mes_gated_workspace_bytes", "mes_delta_linear_gated",
            "mes_step_grad_workspace_bytes", "mes_step_grad", "mes_step_adamw", "mes_noalloc_scratch_bytes",
            "mes_delta_linear_noalloc", "mes_long_segment_tokens"]
 
@@ -122,6 +123,11 @@ def _load() -> ctypes.CDLL:
     lib.mes_pool_acquire.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), c_int, ctypes.POINTER(mes_delta), vp, vp]
     lib.mes_pool_slot_of.restype = c_int
     lib.mes_pool_slot_of.argtypes = [vp, c_int]
+    lib.mes_gated_workspace_bytes.restype = c_sz
+    lib.mes_gated_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.mes_delta_linear_gated.restype = c_int
+    lib.mes_delta_linear_gated.argtypes = [vp, ctypes.POINTER(mes_delta), vp, ctypes.POINTER(mes_delta), c_int, vp, c_int,
+                                           ctypes.POINTER(ctypes.c_int32), vp, vp, c_sz, vp]
     i32p = ctypes.POINTER(ctypes.c_int32)
     lib.mes_pool_slot_layout.restype = c_sz
     lib.mes_pool_slot_layout.argtypes = [c_int, c_int, c_int, c_int, ctypes.POINTER(c_sz)]
@@ -388,6 +394,31 @@ class DeltaLinearMulti:
         _check(lib.mes_delta_linear_multi(lin, self.n, self.E, _ptr(x), T, seg, _ptr(self.ws), self.ws.numel(),
                                           _stream(x.device)))
         return list(ys)
+
+
+class DeltaLinearGated:
+    """Marshalled arguments of mes_delta_linear_gated: h = SiLU(gate layer) * (up layer), one pass, one output."""
+
+    def __init__(self, w_gate_tiled, gate_experts, w_up_tiled, up_experts, max_tokens: int = 64,
+                 workspace: Optional[torch.Tensor] = None):
+        self.w_gate, self.w_up = w_gate_tiled, w_up_tiled
+        self.gate, self.up = list(gate_experts), list(up_experts)
+        self.E = len(self.gate)
+        self.d_in, self.d_out = self.gate[0].d_in, self.gate[0].d_out
+        self.gate_desc = (mes_delta * self.E)(*[e.descriptor() for e in self.gate])
+        self.up_desc = (mes_delta * self.E)(*[e.descriptor() for e in self.up])
+        nbytes = max(lib.mes_gated_workspace_bytes(self.d_in, self.d_out, max_tokens), 16)
+        self.ws = workspace if workspace is not None else torch.empty(nbytes, dtype=torch.uint8, device=w_gate_tiled.device)
+        assert self.ws.numel() >= nbytes
+
+    def __call__(self, x: torch.Tensor, seg_offsets: Sequence[int], h: Optional[torch.Tensor] = None) -> torch.Tensor:
+        T = x.shape[0]
+        if h is None:
+            h = torch.empty((T, self.d_out), dtype=torch.bfloat16, device=x.device)
+        seg = (ctypes.c_int32 * (self.E + 1))(*seg_offsets)
+        _check(lib.mes_delta_linear_gated(_ptr(self.w_gate), self.gate_desc, _ptr(self.w_up), self.up_desc, self.E, _ptr(x), T,
+                                          seg, _ptr(h), _ptr(self.ws), self.ws.numel(), _stream(x.device)))
+        return h
 
 
 class ExpertPool:

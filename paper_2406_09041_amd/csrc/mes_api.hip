@@ -165,9 +165,9 @@ mes_status mes_unpack_delta(const mes_delta* d, float* delta_hat_out, uint8_t* c
   return check_hip(launch_unpack_delta(*d, delta_hat_out, codes_out, (hipStream_t)stream), "mes_unpack_delta");
 }
 
-mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
-                                  const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream) {
-  const char* who = "mes_delta_linear";
+// mes_delta_linear_multi and, with gated != 0 (two layers: gate, up; one output at linears[0].y), mes_delta_linear_gated.
+static mes_status run_linears(const char* who, const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
+                              const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream, int gated) {
   // the measurement hook is one-shot: this call consumes the events whichever way it returns
   const hipEvent_t ev_start = g_ev_start, ev_stop = g_ev_stop;
   g_ev_start = g_ev_stop = nullptr;
@@ -196,18 +196,38 @@ mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int 
   if (T == 0) return MES_OK;
   if (!x) return fail(MES_ERR_NULL, "%s: w_base / x / y is null", who);
   for (int l = 0; l < n_linears; ++l) {
-    if (!linears[l].w_base_tiled || !linears[l].y) return fail(MES_ERR_NULL, "%s: w_base / x / y is null", who);
-    if (!aligned16(linears[l].w_base_tiled) || !aligned16(linears[l].y))
+    const bool has_y = !(gated && l > 0);   // the gated pair has one output
+    if (!linears[l].w_base_tiled || (has_y && !linears[l].y)) return fail(MES_ERR_NULL, "%s: w_base / x / y is null", who);
+    if (!aligned16(linears[l].w_base_tiled) || (has_y && !aligned16(linears[l].y)))
       return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
   }
   if (!aligned16(x)) return fail(MES_ERR_ALIGN, "%s: w_base, x and y must be 16-byte aligned", who);
+  if (gated && d_outs[0] != d_outs[1]) return fail(MES_ERR_SHAPE, "%s: gate and up projection differ in d_out (%d, %d)", who, d_outs[0], d_outs[1]);
   // the streaming path's share is what a call needs; the one-product scratch (sizes asked for with max_tokens >= 192)
   // is used when it is there
-  const size_t need = mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, 1);
+  const size_t need = gated ? gated_workspace_bytes(linears[0].experts[0].d_in, d_outs[0], 1)
+                            : mes_linear_multi_workspace_bytes(linears[0].experts[0].d_in, d_outs, n_linears, 1);
   if (!workspace || workspace_bytes < need) return fail(MES_ERR_WORKSPACE, "%s: workspace needs %zu bytes", who, need);
   if (!aligned16(workspace)) return fail(MES_ERR_ALIGN, "%s: workspace must be 16-byte aligned", who);
-  LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, ev_start, ev_stop};
+  LinearCall c{linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, ev_start, ev_stop, gated};
   return check_hip(launch_delta_linear(c, (hipStream_t)stream), who);
+}
+
+mes_status mes_delta_linear_multi(const mes_linear* linears, int n_linears, int n_experts, const void* x, int T,
+                                  const int32_t* seg_offsets, void* workspace, size_t workspace_bytes, void* stream) {
+  return run_linears("mes_delta_linear", linears, n_linears, n_experts, x, T, seg_offsets, workspace, workspace_bytes, stream, 0);
+}
+
+size_t mes_gated_workspace_bytes(int d_in, int d_out, int max_tokens) {
+  if (d_in <= 0 || d_out <= 0 || max_tokens < 0) return 0;
+  return gated_workspace_bytes(d_in, d_out, max_tokens);
+}
+
+mes_status mes_delta_linear_gated(const void* w_gate_tiled, const mes_delta* gate_experts, const void* w_up_tiled,
+                                  const mes_delta* up_experts, int n_experts, const void* x, int T,
+                                  const int32_t* seg_offsets, void* h, void* workspace, size_t workspace_bytes, void* stream) {
+  const mes_linear pair[2] = {{w_gate_tiled, gate_experts, h}, {w_up_tiled, up_experts, nullptr}};
+  return run_linears("mes_delta_linear_gated", pair, 2, n_experts, x, T, seg_offsets, workspace, workspace_bytes, stream, 1);
 }
 
 mes_status mes_delta_linear(const void* w_base_tiled, const mes_delta* experts, int n_experts, const void* x, int T,

@@ -43,8 +43,10 @@ struct LinearCall {
   void* ws;
   size_t ws_bytes;
   hipEvent_t ev_start, ev_stop;   // measurement hook (nullptr: none)
+  int gated;               // 1: lin[0] = gate, lin[1] = up projection; the one output SiLU(gate) * up goes to lin[0].y
 };
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens);
+size_t gated_workspace_bytes(int d_in, int d_out, int max_tokens);
 int long_segment_tokens();
 hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s);
 

@@ -93,6 +93,10 @@ struct LinearParams {
   int tiles;                              // 16-token tiles of the group that hold tokens
   int n_stage_items, n_items;             // preparation items: tiles * n_chunks stage items, then n_linears * n_vis gathers
   float z;
+  // Gated pair (see launch_delta_linear): lin[0] is the gate, lin[1] the up projection of an MLP block.  The first
+  // half of a workgroup's wavefronts owns row tiles of the gate, the second half the same row tiles of the up
+  // projection, and the workgroup writes SiLU(gate) * up to lin[0].y instead of the two results.
+  int pair;
 };
 
 // One launch serves up to kMaxGroups token groups (256 tokens), in two classes: the groups with many experts (their
@@ -211,6 +215,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// SiLU(gate) * up, element by element, in fp32: SiLU(v) = v / (1 + e^-v).
+__device__ __forceinline__ f32x4 gated(f32x4 gate, f32x4 up) {
+  f32x4 h;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) h[v] = gate[v] / (1.0f + expf(-gate[v])) * up[v];
+  return h;
+}
 
 // ---- preparation ------------------------------------------------------------------------------------
 // The preparation launch: one item per block of 256 threads.  Items [0, n_stage_items) build one token tile of one
@@ -677,7 +689,8 @@ struct LdsPlan {
   static constexpr int kStepBytes = NW * kLaunchSlots * 16 * 4;
   static constexpr int kVisBytes = (kMaxVisits + 1 + 3) / 4 * 16;
   static constexpr int kStages = 2 * kStageLds + 2048;
-  static constexpr int kTotal = kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8 + 256;
+  static constexpr int kSalBytes = 2 * kMaxSlots * 8;   // two tables: a gated pair's workgroup serves two layers
+  static constexpr int kTotal = kStages + kParkBytes + kStepBytes + kVisBytes + kSalBytes + 256;
 };
 
 // One workgroup's work: row group rg, column split sp of token group p, with NA expert slots per sweep.
@@ -689,10 +702,12 @@ __device__ __forceinline__ void stream_rows(const LinearParams& p, char* lds, in
   // sit in a region the compiler predicates with EXEC instead of branching around.
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
-  const PerLinear& L = p.lin[linear_of(p, rg)];
-  int jt = (rg - L.rg_begin) * NW + wave;
-  const bool live = jt < L.n_jt;            // wavefronts past the last row tile recompute the last one and store nothing
-  jt = live ? jt : L.n_jt - 1;
+  constexpr int kHalf = NW / 2;             // gated pair: wavefront w < kHalf and wavefront w + kHalf own the same row tile
+  const bool upper = p.pair && wave >= kHalf;
+  const PerLinear& L = p.pair ? p.lin[upper ? 1 : 0] : p.lin[linear_of(p, rg)];
+  int jt = p.pair ? rg * kHalf + (upper ? wave - kHalf : wave) : (rg - L.rg_begin) * NW + wave;
+  const bool live = jt < L.n_jt && !(p.pair && wave >= 2 * kHalf);   // wavefronts past the last row tile recompute the last one and store nothing
+  jt = jt < L.n_jt ? jt : L.n_jt - 1;
   const int c_begin = p.c_split[sp], c_end = p.c_split[sp + 1];
 
   using Plan = LdsPlan<BITS, NA, NW>;
@@ -706,10 +721,10 @@ __device__ __forceinline__ void stream_rows(const LinearParams& p, char* lds, in
   float (*step_lds)[kLaunchSlots][16] = reinterpret_cast<float (*)[kLaunchSlots][16]>(lds + kStages + kParkBytes);
   int* const vis_lds = reinterpret_cast<int*>(lds + kStages + kParkBytes + kStepBytes);
   uint64_t* const sal_lds = reinterpret_cast<uint64_t*>(lds + kStages + kParkBytes + kStepBytes + kVisBytes);
-  char* const warm_lds = lds + kStages + kParkBytes + kStepBytes + kVisBytes + kMaxSlots * 8;
+  char* const warm_lds = lds + kStages + kParkBytes + kStepBytes + kVisBytes + Plan::kSalBytes;
 
   using S = Stream<BITS, TT, NA, NW>;
-  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), &step_lds[wave][0][0], vis_lds, sal_lds, wave >= 4);   // wavefronts w and w + 4 share a SIMD
+  S ws(p, L, lane, jt, park_all + wave * (NA * code_block_bytes(BITS)), &step_lds[wave][0][0], vis_lds, sal_lds + (upper ? kMaxSlots : 0), wave >= 4);   // wavefronts w and w + 4 share a SIMD
   f32x4 (&acc_base)[TT] = ws.acc_base;
   f32x4 (&acc_raw)[TT] = ws.acc_raw;
   const uint32_t (&slot_tok)[TT] = ws.slot_tok;
@@ -746,11 +761,14 @@ __device__ __forceinline__ void stream_rows(const LinearParams& p, char* lds, in
   int vis_v = 0;
   uint64_t sal_v = 0;
   if (tid <= kMaxVisits) vis_v = p.vis_info[tid];
-  if (tid < kMaxSlots) sal_v = reinterpret_cast<uint64_t>(L.sal[tid]);
+  // (the salient tile table is per layer: wavefront 0 writes its layer's, and in a gated pair the first wavefront of
+  // the upper half writes the other layer's behind it)
+  const bool fills_sal = lane < kMaxSlots && (wave == 0 || (p.pair && wave == kHalf));
+  if (fills_sal) sal_v = reinterpret_cast<uint64_t>(L.sal[lane]);
   ws.sal_begin(sp);
   if (st_a < kLaunchSlots) *reinterpret_cast<f32x4*>(&step_lds[wave][st_a][4 * (lane & 3)]) = st_v;
   if (tid <= kMaxVisits) vis_lds[tid] = vis_v;
-  if (tid < kMaxSlots) sal_lds[tid] = sal_v;
+  if (fills_sal) sal_lds[(wave == 0 ? 0 : kMaxSlots) + lane] = sal_v;
 
   ws.template park<0>();
   stage_barrier<0>();
@@ -811,15 +829,31 @@ __device__ __forceinline__ void stream_rows(const LinearParams& p, char* lds, in
     f32x4* part = p.partial + ((size_t)rg * p.nsplit + sp) * (4 * NT);
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) part[ws.pt(tt) * NT + tid] = o[tt];
-  } else if (live) {
+  } else {
+    if (p.pair) {
+      // The up projection's tiles cross over to the wavefronts that hold the gate's through LDS.  The activation
+      // stages are free: the loop's last barrier had every wavefront done with them.
+      f32x4* xch = reinterpret_cast<f32x4*>(lds);
+      if (upper && wave < 2 * kHalf) {
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-      const int t = p.t0 + 16 * ws.pt(tt) + n, j = 16 * jt + 4 * g;
-      if (t < p.T && j < L.d_out) {
-        uint2 pk;
-        pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
-        pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
-        *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
+        for (int tt = 0; tt < TT; ++tt) xch[((wave - kHalf) * 4 + ws.pt(tt)) * 64 + lane] = o[tt];
+      }
+      __syncthreads();
+      if (!upper) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) o[tt] = gated(o[tt], xch[(wave * 4 + ws.pt(tt)) * 64 + lane]);
+      }
+    }
+    if (live && !upper) {
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        const int t = p.t0 + 16 * ws.pt(tt) + n, j = 16 * jt + 4 * g;
+        if (t < p.T && j < L.d_out) {
+          uint2 pk;
+          pk.x = f32_to_bf16(o[tt][0]) | (f32_to_bf16(o[tt][1]) << 16);
+          pk.y = f32_to_bf16(o[tt][2]) | (f32_to_bf16(o[tt][3]) << 16);
+          *reinterpret_cast<uint2*>(L.y + (size_t)t * L.d_out + j) = pk;
+        }
       }
     }
   }
@@ -858,10 +892,18 @@ __global__ __launch_bounds__(64 * NW) void k_reduce_splits(const LaunchParams mp
   const f32x4* part = p.partial + (size_t)rg * p.nsplit * (4 * NT) + tt * NT + tid;
   f32x4 o = {0, 0, 0, 0};
   for (int s = 0; s < p.nsplit; ++s) o += part[(size_t)s * (4 * NT)];
-  const PerLinear& L = p.lin[linear_of(p, rg)];
-  const int jt = (rg - L.rg_begin) * NW + wave;
+  constexpr int kHalf = NW / 2;
+  const bool upper = p.pair && wave >= kHalf;
+  if (p.pair) {   // gated pair: the up projection's sums cross over to the threads that hold the gate's
+    __shared__ f32x4 xch[kHalf * 64];
+    if (upper && wave < 2 * kHalf) xch[(wave - kHalf) * 64 + lane] = o;
+    __syncthreads();
+    if (!upper) o = gated(o, xch[wave * 64 + lane]);
+  }
+  const PerLinear& L = p.pair ? p.lin[0] : p.lin[linear_of(p, rg)];
+  const int jt = p.pair ? rg * kHalf + wave : (rg - L.rg_begin) * NW + wave;
   const int t = p.t0 + 16 * tt + n, j = 16 * jt + 4 * g;
-  if (jt < L.n_jt && t < p.T && j < L.d_out) {
+  if (!upper && jt < L.n_jt && t < p.T && j < L.d_out) {
     uint2 pk;
     pk.x = f32_to_bf16(o[0]) | (f32_to_bf16(o[1]) << 16);
     pk.y = f32_to_bf16(o[2]) | (f32_to_bf16(o[3]) << 16);
@@ -880,17 +922,25 @@ struct Plan {
 
 inline int row_groups_of(int d_out, int nw) { return (ceil_to(d_out, kRowPad) / 16 + nw - 1) / nw; }
 
+// Row groups of a launch.  A gated pair's workgroups hold nw / 2 row tiles of each of the two layers.
+inline int row_groups_total(const int* d_out, int n_linears, int nw, bool pair) {
+  if (pair) return row_groups_of(d_out[0], nw / 2);
+  int rgs = 0;
+  for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], nw);
+  return rgs;
+}
+
 // Pure function of the shapes (not of bits or T), so the workspace size is known up front.
 // One workgroup runs per compute unit (256 of them).  The chunks are split over `nsplit` workgroups so that
 // the grid fills the largest part of the last round of 256, with at least four chunks per workgroup and,
 // among equals, few splits (every split writes and re-reads a partial output tile).
-Plan plan_for(int d_in, const int* d_out, int n_linears) {
+Plan plan_for(int d_in, const int* d_out, int n_linears, bool pair) {
   const int n_chunks = ceil_to(d_in, kColPad) / kChunk;
   Plan best{1, kMaxWaves};
   double best_cost = 1e30;
   for (int nw = kMaxWaves; nw >= 6; --nw) {
-    int rgs = 0;
-    for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], nw);
+    if (pair && nw % 2) continue;   // a gated pair splits the wavefronts evenly between its two layers
+    const int rgs = row_groups_total(d_out, n_linears, nw, pair);
     for (int ns = 1; ns <= kMaxSplits && (ns == 1 || ns * 4 <= n_chunks); ++ns) {
       const long wgs = (long)rgs * ns;
       const long rounds = (wgs + 255) / 256;
@@ -910,10 +960,9 @@ struct WorkspaceLayout {
   size_t xs_bytes;
 };
 
-WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears) {
-  const Plan pl = plan_for(d_in, d_out, n_linears);
-  int rgs = 0;
-  for (int l = 0; l < n_linears; ++l) rgs += row_groups_of(d_out[l], pl.nw);
+WorkspaceLayout workspace_layout(int d_in, const int* d_out, int n_linears, bool pair) {
+  const Plan pl = plan_for(d_in, d_out, n_linears, pair);
+  const int rgs = row_groups_total(d_out, n_linears, pl.nw, pair);
   const int pi = ceil_to(d_in, kColPad);
   WorkspaceLayout w;
   size_t off = 0;
@@ -976,8 +1025,13 @@ hipError_t launch_reduce(const LaunchParams& mp, int tt, int nw, hipStream_t s) 
 constexpr int kPrefillMin = 192;
 int long_segment_tokens() { return kPrefillMin; }
 
+size_t gated_workspace_bytes(int d_in, int d_out, int max_tokens) {
+  const int d[2] = {d_out, d_out};
+  return groups_for(max_tokens) * workspace_layout(d_in, d, 2, true).total;   // the gated pair always streams
+}
+
 size_t linear_workspace_bytes(int d_in, const int* d_out, int n_linears, int max_tokens) {
-  const size_t per_group = workspace_layout(d_in, d_out, n_linears).total;
+  const size_t per_group = workspace_layout(d_in, d_out, n_linears, false).total;
   // the one-product scratch always sits behind kMaxGroups groups' worth (a workspace that has it was sized for
   // at least kPrefillMin tokens, i.e. for all the groups)
   if (max_tokens >= kPrefillMin) return kMaxGroups * per_group + prefill_scratch_bytes(d_in, max_tokens);
@@ -988,7 +1042,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   const mes_delta& d0 = c.lin[0].experts[0];
   int d_outs[kMaxLinears];
   for (int l = 0; l < c.n_linears; ++l) d_outs[l] = c.lin[l].experts[0].d_out;
-  const WorkspaceLayout wl = workspace_layout(d0.d_in, d_outs, c.n_linears);
+  const bool pair = c.gated != 0;   // lin[0] = gate, lin[1] = up, one output SiLU(gate) * up at lin[0].y
+  const WorkspaceLayout wl = workspace_layout(d0.d_in, d_outs, c.n_linears, pair);
   char* ws = reinterpret_cast<char*>(c.ws);
   // token groups one launch may hold: as many as the workspace has room for
   const int max_groups = (int)(c.ws_bytes / wl.total < (size_t)kMaxGroups ? c.ws_bytes / wl.total : (size_t)kMaxGroups);
@@ -1003,7 +1058,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   p0.k = d0.k;
   p0.bits = d0.bits;
   p0.z = d0.grid == MES_GRID_SYM ? (float)(1 << (d0.bits - 1)) - 0.5f : (float)(1 << (d0.bits - 1));
-  const Plan pl = plan_for(d0.d_in, d_outs, c.n_linears);
+  p0.pair = pair ? 1 : 0;
+  const Plan pl = plan_for(d0.d_in, d_outs, c.n_linears, pair);
   int rgs = 0;
   for (int l = 0; l < kMaxLinears; ++l) {
     PerLinear& L = p0.lin[l];
@@ -1016,6 +1072,7 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     if (l < c.n_linears) rgs += row_groups_of(d_outs[l], pl.nw);
     L.rg_end = rgs;
   }
+  if (pair) rgs = row_groups_total(d_outs, 2, pl.nw, true);
   p0.nsplit = pl.nsplit;
   for (int sp = 0; sp <= pl.nsplit; ++sp) p0.c_split[sp] = (int16_t)((long)sp * p0.n_chunks / pl.nsplit);
   LaunchParams mp;
@@ -1151,7 +1208,8 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
   for (int e = 0; e < c.n_experts; ++e)
     if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_tokens += c.seg[e + 1] - c.seg[e];
   const size_t scratch_at = kMaxGroups * wl.total;
-  const bool can_prefill = long_tokens > 0 && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, long_tokens);
+  // (a gated pair always streams: the one-product path has no gated epilogue)
+  const bool can_prefill = !pair && long_tokens > 0 && c.ws_bytes >= scratch_at + prefill_scratch_bytes(d0.d_in, long_tokens);
   // the long segments of every linear in one go (up to 8 experts per launch), then the streaming ranges between them
   int cursor = 0;
   if (can_prefill) {

@@ -449,6 +449,62 @@ def test_on_demand_swapping_gives_the_resident_result():
     assert nbytes == misses * (mes.codes_bytes(d_in, d_out, bits) + 4 * d_out + mes.salient_bytes(d_out, k) + 4 * k)
 
 
+def gated_case(d_in, d_out, seg, k, bits, seed, device="cpu", grid=0):
+    """Two layers over the same activations and routing (gate, up), oracle result and HIP result of the gated call."""
+    wg = synth.small_case(d_in, d_out, seg, k, bits, seed=seed, device=device)
+    wu = synth.small_case(d_in, d_out, seg, k, bits, seed=seed + 1, device=device)
+    x = wg.x.to(DEV)
+    packed = []
+    for wl in (wg, wu):
+        packed.append((mes.mes_pack_base(wl.w_base.to(DEV)),
+                       [mes.mes_pack_delta(ex.delta.to(DEV), ex.salient_idx if k else None, bits, grid) for ex in wl.experts]))
+    lin = mes.DeltaLinearGated(packed[0][0], packed[0][1], packed[1][0], packed[1][1], max_tokens=seg[-1])
+    h = lin(x, seg)
+    torch.cuda.synchronize()
+    return wg, wu, packed, h
+
+
+@pytest.mark.parametrize("d_in,d_out,seg,k,bits,grid", [
+    (264, 72, [0, 3, 3, 20, 37], 5, 2, 0),               # ragged shape, an empty segment, one row group half empty
+    (4096, 192, [0, 7, 30, 31, 50, 61], 64, 2, 0),       # the columns are split over workgroups: the reduction applies the gate
+    (1160, 200, [0, 5, 5, 21, 40, 64, 150], 24, 4, 1),   # 4-bit codes, Eq. 1 grid, three token groups
+    (520, 1024, [0, 300], 16, 3, 0),                     # a long segment: the gated call streams it all the same
+    (640, 80, [0] + [i + 1 for i in range(20)], 24, 1, 0),   # 20 experts with one token each, 1 bit
+])
+def test_gated_mlp_input_matches_the_oracle(d_in, d_out, seg, k, bits, grid):
+    """h = SiLU(y_gate) * y_up in one pass: against the fp64 oracle (which rounds nothing on the way) on every
+    element, within one bf16 ulp on all but a few per thousand (streaming arithmetic: exact products, fp32 sums, one
+    rounding)."""
+    wg, wu, packed, h = gated_case(d_in, d_out, seg, k, bits, seed=31 + bits, grid=grid)
+    x64 = wg.x.double().numpy()
+    h_ref = O.gated_mlp_input(x64, wg.w_base.double().numpy(), oracle_experts(wg, grid), wu.w_base.double().numpy(),
+                              oracle_experts(wu, grid), seg)
+    assert rel_fro(h, h_ref) <= TOL
+    PC.assert_streaming_rows(h.double().cpu().numpy(), h_ref, ("gated", d_in, d_out, bits))
+    # and the two layers alone, combined on the host in fp64 from their bf16 outputs, agree to bf16 accuracy
+    yg = mes.mes_delta_linear(packed[0][0], packed[0][1], wg.x.to(DEV), seg).double().cpu().numpy()
+    yu = mes.mes_delta_linear(packed[1][0], packed[1][1], wg.x.to(DEV), seg).double().cpu().numpy()
+    assert rel_fro(h, O.silu(yg) * yu) <= 2 * TOL
+
+
+def test_gated_mlp_input_at_full_size():
+    """gate_proj and up_proj of the 16-expert decode batch (4096 -> 14336, 64 tokens, Zipf routing) through the gated
+    call; the oracle recomputes a seeded sample of output channels."""
+    wg = synth.config4_linear("gate_proj", device=DEV)
+    wu = synth.config4_linear("up_proj", device=DEV)
+    assert torch.equal(wg.x, wu.x) and wg.seg_offsets == wu.seg_offsets
+    packed = [(mes.mes_pack_base(wl.w_base), [mes.mes_pack_delta(ex.delta, ex.salient_idx, wl.bits) for ex in wl.experts]) for wl in (wg, wu)]
+    h = mes.DeltaLinearGated(packed[0][0], packed[0][1], packed[1][0], packed[1][1], 64)(wg.x, wg.seg_offsets)
+    torch.cuda.synchronize()
+    g = torch.Generator().manual_seed(123)
+    rows = torch.sort(torch.randperm(wg.d_out, generator=g)[:128]).values.to(DEV)
+    x64 = wg.x.double().cpu().numpy()
+    h_ref = O.gated_mlp_input(x64, wg.w_base[rows].double().cpu().numpy(), oracle_experts(wg, rows=rows),
+                              wu.w_base[rows].double().cpu().numpy(), oracle_experts(wu, rows=rows), wg.seg_offsets)
+    assert rel_fro(h[:, rows], h_ref) <= TOL
+    PC.assert_streaming_rows(h[:, rows].double().cpu().numpy(), h_ref, "gated gate+up at full size")
+
+
 def test_layer_spanning_pool_with_prefetch_gives_the_resident_result():
     """A pool whose slots hold an expert's deltas of three linear layers (two of them read the same activations and go
     through one fused call), one pinned blob and one copy per expert.  After every acquire the next batch's experts

@@ -382,6 +382,42 @@ def test_output_error_bound_from_half_step():
 
 # ---------------------------------------------------------------- Eq. 2: salient selection
 
+def test_silu_closed_forms_and_the_gated_input():
+    """SiLU against what the definition fixes: SiLU(0) = 0, SiLU(v) - SiLU(-v) = v, SiLU(ln 3) = 3/4 ln 3,
+    SiLU(v) = v sigmoid(v) via tanh, its derivative at 0 is 1/2, v -> v for large v and -> 0 for large -v without
+    overflow; and the gated input is the element-wise product of SiLU of one layer and the other layer, not the
+    other way round (a swapped pair fails)."""
+    v = np.linspace(-30, 30, 2001)
+    assert O.silu(np.array([0.0]))[0] == 0.0
+    np.testing.assert_allclose(O.silu(v) - O.silu(-v), v, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(O.silu(np.array([np.log(3.0)]))[0], 0.75 * np.log(3.0), rtol=1e-15)
+    np.testing.assert_allclose(O.silu(v), v * 0.5 * (1.0 + np.tanh(0.5 * v)), rtol=1e-12, atol=1e-14)   # (1 + tanh cancels for very negative v)
+    h = 1e-6
+    np.testing.assert_allclose((O.silu(np.array([h]))[0] - O.silu(np.array([-h]))[0]) / (2 * h), 0.5, rtol=1e-9)
+    big = O.silu(np.array([800.0, -800.0]))
+    assert big[0] == 800.0 and big[1] == 0.0 and np.all(np.isfinite(big))
+    # minimum of SiLU: at v with 1 + e^-v (1 + v) ... = 0, value about -0.27846
+    assert abs(O.silu(v).min() + 0.2784645) < 1e-4
+    rng = np.random.default_rng(5)
+    d_in, d_out, T = 24, 6, 5
+    x = rng.standard_normal((T, d_in))
+    wg, wu = rng.standard_normal((d_out, d_in)), rng.standard_normal((d_out, d_in))
+    def expert(seed):
+        r = np.random.default_rng(seed)
+        return dict(codes=r.integers(0, 4, (d_out, d_in)).astype(np.uint8), step=(0.01 + r.random(d_out)).astype(np.float32),
+                    salient=np.zeros((d_out, 0), np.float16), salient_idx=np.zeros(0, np.int32), bits=2, grid=O.GRID_SYM)
+    eg, eu = [expert(1), expert(2)], [expert(3), expert(4)]
+    seg = [0, 2, 5]
+    got = O.gated_mlp_input(x, wg, eg, wu, eu, seg)
+    yg, yu = O.delta_linear(x, wg, eg, seg), O.delta_linear(x, wu, eu, seg)
+    want = np.empty_like(yg)
+    for t in range(T):
+        for j in range(d_out):
+            want[t, j] = yg[t, j] / (1.0 + np.exp(-yg[t, j])) * yu[t, j]
+    np.testing.assert_allclose(got, want, rtol=1e-13)
+    assert np.abs(got - O.gated_mlp_input(x, wu, eu, wg, eg, seg)).max() > 1e-3
+
+
 def test_selection_matches_brute_force_on_tiny_layers():
     for seed, (d_out, d_in, n, k, bits, grid) in enumerate([(6, 10, 5, 3, 2, O.GRID_SYM), (8, 16, 7, 4, 3, O.GRID_EQ1),
                                                             (5, 12, 4, 2, 1, O.GRID_SYM)]):
