@@ -55,6 +55,11 @@ __device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// The barrier between two steps: waits for this wavefront's LDS traffic only.  (__syncthreads() would also wait for
+// the memory loads in flight: the weights a builder has just requested for a later step, the activation copies a
+// multiplier keeps ahead of itself -- a full memory round trip per step.)
+__device__ __forceinline__ void step_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct TileParams {
   const uint16_t* x;
   const int32_t* sidx[kMaxSegs];
@@ -218,11 +223,11 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
     for (int st = st0; st < st1; st += 2) {
       build(1, st + 1);
       fetch(1, st + 3);
-      __syncthreads();
+      step_barrier();
       if (st + 1 >= st1) break;
       build(0, st + 2);
       fetch(0, st + 4);
-      __syncthreads();
+      step_barrier();
     }
     return;
   }
@@ -276,7 +281,7 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
         for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[rt & 1], xb[tt], acc[rt][tt]);
       }
     }
-    __syncthreads();
+    step_barrier();
   }
   asm volatile("s_waitcnt vmcnt(0)" : : : "memory");     // the surplus copies must land before the LDS is given back
 
