@@ -106,7 +106,11 @@ size_t mes_codes_bytes(int d_in, int d_out, int bits);   /* packed low-bit codes
 size_t mes_salient_bytes(int d_out, int k);              /* tiled fp16 salient columns          */
 size_t mes_pack_workspace_bytes(void);
 size_t mes_select_workspace_bytes(int n, int d_in, int d_out);
-/* Workspace of mes_delta_linear / _multi.  Asked for with max_tokens >= 192 it includes room for the long-segment
+/* Workspace of mes_delta_linear / _multi.  Tokens are streamed in groups of 64 and one launch serves as many groups
+ * as the workspace has slices for: one slice for max_tokens <= 64, two for <= 128, four above that (a slice: the
+ * group's prepared activations, gathered salient activations and split-column partial sums).  A larger workspace
+ * than a call needs is fine; a smaller one (at least one slice) is accepted and costs launches, not correctness.
+ * Asked for with max_tokens >= 192 it also includes room for the long-segment
  * path (the segment's activations re-tiled, about 4 d_in bytes per token, and up to 64 MiB of partial sums): an
  * expert segment of 192 tokens or more is then computed as one dense product x (W + Delta~)^T (Eq. 4 before
  * decoupling; the expert's effective weight is formed in registers, block by block, as a matrix-core operand),

@@ -1,8 +1,9 @@
 // The serving hot path (Eq. 4, batched across experts):
 //   y[t] = x[t] W^T + step_e .* (x_ns[t] (U_e - z)^T) + x_s[t] D_e^T
-// for groups of up to 64 tokens.  Per group: one small preparation launch, the main streaming launch and, only when
-// the columns had to be split over workgroups, a small reduction launch.  (Letting the last workgroup of a row group do that reduction inside the
-// main kernel was measured and is slower: the device-wide hand-over costs more than the extra launch.)
+// for token groups of up to 64 tokens, up to four groups per launch.  Per launch: one small preparation launch, the
+// main streaming launch and, only when the columns had to be split over workgroups, a small reduction launch.
+// (Letting the last workgroup of a row group do that reduction inside the main kernel was measured and is slower:
+// the device-wide hand-over costs more than the extra launch.  Likewise the preparation folded into the main kernel.)
 //
 // Main kernel.  A workgroup of eight wavefronts (two per SIMD: while one waits for memory or for the
 // matrix core the other issues) owns 128 output channels, one 16-row tile per wavefront, and a range of

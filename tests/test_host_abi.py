@@ -163,6 +163,29 @@ def test_noalloc_entry_point_argument_errors():
         assert 0 < lib.mes_linear_workspace_bytes(d_in, d_out, 1) <= lib.mes_noalloc_scratch_bytes()
 
 
+def test_gated_entry_point_argument_errors_and_workspace_sizes():
+    """Host-side validation of mes_delta_linear_gated, and the slices of the streaming workspaces: one 64-token group
+    for up to 64 tokens, two up to 128, four above."""
+    seg = (ctypes.c_int32 * 2)(0, 4)
+    g, u = _desc(), _desc()
+    ws = lib.mes_gated_workspace_bytes(g.d_in, g.d_out, 4)
+    call = lambda gate=g, up=u, h=FAKE, wsp=FAKE, n=ws: lib.mes_delta_linear_gated(
+        FAKE, ctypes.byref(gate) if gate is not None else None, FAKE, ctypes.byref(up) if up is not None else None, 1, FAKE, 4, seg,
+        h, wsp, n, None)
+    assert call(gate=None) == 1 and call(up=None) == 1 and call(h=None) == 1
+    assert call(up=_desc(d_out=g.d_out * 2)) == 2 and b"d_out" in lib.mes_last_error()
+    assert call(up=_desc(bits=3)) == 2
+    assert call(wsp=None) == 7 and call(n=ws - 1) == 7
+    assert lib.mes_gated_workspace_bytes(0, 64, 4) == 0
+    one = lib.mes_linear_workspace_bytes(4096, 4096, 64)
+    assert lib.mes_linear_workspace_bytes(4096, 4096, 1) == one
+    assert lib.mes_linear_workspace_bytes(4096, 4096, 65) == 2 * one == lib.mes_linear_workspace_bytes(4096, 4096, 128)
+    assert lib.mes_linear_workspace_bytes(4096, 4096, 129) == 4 * one
+    assert lib.mes_linear_workspace_bytes(4096, 4096, 192) > 4 * one            # + the one-product scratch
+    g1 = lib.mes_gated_workspace_bytes(4096, 14336, 64)
+    assert lib.mes_gated_workspace_bytes(4096, 14336, 256) == 4 * g1
+
+
 def test_copy_probe_argument_errors():
     lib = B.lib
     assert lib.mes_copy_probe(None, 16, 16, None) == 1
