@@ -60,8 +60,8 @@ hipError_t launch_adamw(float* step, const float* grad, float* m, float* v, int 
 
 // ---- implemented in mes_prefill.hip ------------------------------------------------------------
 size_t prefill_scratch_bytes(int d_in, int max_tokens);
-hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
-                                   const int32_t* seg, const void* x, void* y, void* scratch, hipEvent_t ev_start,
+hipError_t launch_prefill_segments(const mes_linear* lin, int n_linears, const int* seg_experts, int n_seg,
+                                   const int32_t* seg, const void* x, void* scratch, hipEvent_t ev_start,
                                    hipEvent_t ev_stop, bool* first_kernel, hipStream_t s);
 
 }  // namespace mes

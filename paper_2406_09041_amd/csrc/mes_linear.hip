@@ -1217,11 +1217,9 @@ hipError_t launch_delta_linear(const LinearCall& c, hipStream_t s) {
     int long_experts[MES_MAX_EXPERTS], n_long = 0;
     for (int e = 0; e < c.n_experts; ++e)
       if (c.seg[e + 1] - c.seg[e] >= kPrefillMin) long_experts[n_long++] = e;
-    for (int l = 0; l < c.n_linears; ++l) {
-      hipError_t err = launch_prefill_segments(c.lin[l].w_base_tiled, c.lin[l].experts, long_experts, n_long, c.seg, c.x,
-                                               c.lin[l].y, ws + scratch_at, c.ev_start, c.ev_stop, &first_kernel, s);
-      if (err != hipSuccess) return err;
-    }
+    hipError_t perr = launch_prefill_segments(c.lin, c.n_linears, long_experts, n_long, c.seg, c.x, ws + scratch_at,
+                                              c.ev_start, c.ev_stop, &first_kernel, s);
+    if (perr != hipSuccess) return perr;
     for (int i = 0; i < n_long; ++i) {
       const int e = long_experts[i];
       hipError_t err = run_range(cursor, c.seg[e]);

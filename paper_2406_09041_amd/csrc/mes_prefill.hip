@@ -65,6 +65,7 @@ struct TileParams {
   const int32_t* sidx[kMaxSegs];
   int t_begin[kMaxSegs], t_end[kMaxSegs], tb0[kMaxSegs + 1];
   int n_seg, k, d_in, n_kb_main, n_tq;
+  int kb_begin;             // this launch writes the k blocks kb_begin .. kb_begin + n_blk / n_tq - 1
   size_t n_blk;
   u32x4* xt;
 };
@@ -77,7 +78,7 @@ __global__ void k_prefill_tile_x(const TileParams p) {
   const int lane = threadIdx.x & 63;
   const size_t blk = (size_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (blk >= p.n_blk) return;
-  const int tq = (int)(blk % p.n_tq), kbi = (int)(blk / p.n_tq);
+  const int tq = (int)(blk % p.n_tq), kbi = p.kb_begin + (int)(blk / p.n_tq);
   int sg = 0;
   while (sg + 1 < p.n_seg && tq >= 16 * p.tb0[sg + 1]) ++sg;
   const int t = p.t_begin[sg] + 16 * (tq - 16 * p.tb0[sg]) + (lane & 15);
@@ -102,7 +103,7 @@ __global__ void k_prefill_tile_x(const TileParams p) {
       v = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
     }
   }
-  p.xt[blk * 64 + lane] = v;
+  p.xt[((size_t)kbi * p.n_tq + tq) * 64 + lane] = v;
 }
 
 // What a builder keeps in flight for one step (128 input channels, or 128 salient ranks) of its row tile.
@@ -384,74 +385,89 @@ size_t prefill_scratch_bytes(int d_in, int max_tokens) {
   return (xt + 255) / 256 * 256 + tiles;
 }
 
-// y rows of the n_seg long segments seg_experts[i] (expert numbers; rows seg[e] .. seg[e + 1]) of one linear, each with
-// its own expert's delta, up to kMaxSegs per launch.  scratch: prefill_scratch_bytes(d_in, >= all their tokens).
+// y rows of the n_seg long segments seg_experts[i] (expert numbers; rows seg[e] .. seg[e + 1]) of the n_linears layers
+// of a call (they read the same x and routing), each layer with its own experts' deltas, up to kMaxSegs segments per
+// launch.  The segments' activations are re-tiled once for all layers; the gathered salient activations, which
+// depend on the layer's salient sets, once per layer into the same place (the launches are stream-ordered).
+// scratch: prefill_scratch_bytes(d_in, >= all their tokens).
 // ev_start / ev_stop (measurement hook, may be null): recorded immediately before the first fused kernel (only while
 // *first_kernel is set, which this clears) and immediately after every fused kernel and its reduction.
-hipError_t launch_prefill_segments(const void* w_base_tiled, const mes_delta* experts, const int* seg_experts, int n_seg,
-                                   const int32_t* seg, const void* x, void* y, void* scratch, hipEvent_t ev_start,
+hipError_t launch_prefill_segments(const mes_linear* lin, int n_linears, const int* seg_experts, int n_seg,
+                                   const int32_t* seg, const void* x, void* scratch, hipEvent_t ev_start,
                                    hipEvent_t ev_stop, bool* first_kernel, hipStream_t s) {
   char* ws = reinterpret_cast<char*>(scratch);
   for (int first = 0; first < n_seg; first += kMaxSegs) {
     const int ns = n_seg - first < kMaxSegs ? n_seg - first : kMaxSegs;
-    const mes_delta& d = experts[seg_experts[first]];   // shape, bits, grid and k are the same for all experts of a linear
-    PrefillParams p;
-    TileParams tp;
-    int n_tb = 0;
-    for (int i = 0; i < kMaxSegs; ++i) {
-      const mes_delta& de = experts[seg_experts[first + (i < ns ? i : 0)]];
-      const int e = seg_experts[first + (i < ns ? i : 0)];
-      p.codes[i] = reinterpret_cast<const uint32_t*>(de.codes);
-      p.step[i] = de.step;
-      p.sal[i] = reinterpret_cast<const u32x4*>(de.salient);
-      tp.sidx[i] = de.salient_idx;
-      p.t_begin[i] = tp.t_begin[i] = seg[e];
-      p.t_end[i] = tp.t_end[i] = seg[e + 1];
-      p.tb0[i] = tp.tb0[i] = n_tb;
-      if (i < ns) n_tb += (seg[e + 1] - seg[e] + 255) / 256;
+    for (int l = 0; l < n_linears; ++l) {
+      const mes_delta* experts = lin[l].experts;
+      const mes_delta& d = experts[seg_experts[first]];   // shape, bits, grid and k are the same for all experts of a linear
+      PrefillParams p;
+      TileParams tp;
+      int n_tb = 0;
+      for (int i = 0; i < kMaxSegs; ++i) {
+        const mes_delta& de = experts[seg_experts[first + (i < ns ? i : 0)]];
+        const int e = seg_experts[first + (i < ns ? i : 0)];
+        p.codes[i] = reinterpret_cast<const uint32_t*>(de.codes);
+        p.step[i] = de.step;
+        p.sal[i] = reinterpret_cast<const u32x4*>(de.salient);
+        tp.sidx[i] = de.salient_idx;
+        p.t_begin[i] = tp.t_begin[i] = seg[e];
+        p.t_end[i] = tp.t_end[i] = seg[e + 1];
+        p.tb0[i] = tp.tb0[i] = n_tb;
+        if (i < ns) n_tb += (seg[e + 1] - seg[e] + 255) / 256;
+      }
+      p.tb0[kMaxSegs] = tp.tb0[kMaxSegs] = n_tb;
+      for (int i = ns; i <= kMaxSegs; ++i) p.tb0[i] = tp.tb0[i] = n_tb;
+      p.n_seg = tp.n_seg = ns;
+      const PrefillPlan pl = prefill_plan(d.d_in, d.d_out, d.k, n_tb);
+      p.base = reinterpret_cast<const u32x4*>(lin[l].w_base_tiled);
+      p.xt = reinterpret_cast<const u32x4*>(ws);
+      p.y = reinterpret_cast<uint16_t*>(lin[l].y);
+      p.tiles = reinterpret_cast<f32x4*>(ws + pl.tiles_at);
+      p.d_out = d.d_out;
+      p.n_jt = ceil_to(d.d_out, kRowPad) / 16;
+      p.n_chunks = pl.n_chunks;
+      p.n_sb = ceil_to(d.k, kSalPad) / 32;
+      p.n_ssteps = pl.n_ssteps;
+      p.n_tq = pl.n_tq;
+      p.steps_per_split = pl.steps_per_split;
+      p.n_split = pl.n_split;
+      p.z = d.grid == MES_GRID_SYM ? (float)(1 << (d.bits - 1)) - 0.5f : (float)(1 << (d.bits - 1));
+      tp.x = reinterpret_cast<const uint16_t*>(x);
+      tp.k = d.k;
+      tp.d_in = d.d_in;
+      tp.n_kb_main = 4 * pl.n_chunks;
+      tp.n_tq = pl.n_tq;
+      tp.xt = reinterpret_cast<u32x4*>(ws);
+      hipError_t e = hipSuccess;
+      if (l == 0) {   // the input channels: the same for every layer of the call
+        tp.kb_begin = 0;
+        tp.n_blk = (size_t)tp.n_kb_main * pl.n_tq;
+        k_prefill_tile_x<<<(unsigned)((tp.n_blk + 3) / 4), 256, 0, s>>>(tp);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
+      if (pl.n_ssteps > 0) {   // this layer's gathered salient channels, behind them
+        tp.kb_begin = tp.n_kb_main;
+        tp.n_blk = (size_t)4 * pl.n_ssteps * pl.n_tq;
+        k_prefill_tile_x<<<(unsigned)((tp.n_blk + 3) / 4), 256, 0, s>>>(tp);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
+      const dim3 grid(pl.n_rg, pl.n_tb, pl.n_split);
+      if (ev_start && *first_kernel && (e = hipEventRecord(ev_start, s)) != hipSuccess) return e;
+      *first_kernel = false;
+      switch (d.bits) {
+        case 1: e = launch_fused<1>(p, pl, grid, s); break;
+        case 2: e = launch_fused<2>(p, pl, grid, s); break;
+        case 3: e = launch_fused<3>(p, pl, grid, s); break;
+        default: e = launch_fused<4>(p, pl, grid, s); break;
+      }
+      if (e != hipSuccess) return e;
+      if (pl.n_split > 1) {
+        k_prefill_reduce<8, 4><<<dim3(grid.x, grid.y, 32), 256, 0, s>>>(p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
+      if (ev_stop && (e = hipEventRecord(ev_stop, s)) != hipSuccess) return e;
     }
-    p.tb0[kMaxSegs] = tp.tb0[kMaxSegs] = n_tb;
-    for (int i = ns; i <= kMaxSegs; ++i) p.tb0[i] = tp.tb0[i] = n_tb;
-    p.n_seg = tp.n_seg = ns;
-    const PrefillPlan pl = prefill_plan(d.d_in, d.d_out, d.k, n_tb);
-    p.base = reinterpret_cast<const u32x4*>(w_base_tiled);
-    p.xt = reinterpret_cast<const u32x4*>(ws);
-    p.y = reinterpret_cast<uint16_t*>(y);
-    p.tiles = reinterpret_cast<f32x4*>(ws + pl.tiles_at);
-    p.d_out = d.d_out;
-    p.n_jt = ceil_to(d.d_out, kRowPad) / 16;
-    p.n_chunks = pl.n_chunks;
-    p.n_sb = ceil_to(d.k, kSalPad) / 32;
-    p.n_ssteps = pl.n_ssteps;
-    p.n_tq = pl.n_tq;
-    p.steps_per_split = pl.steps_per_split;
-    p.n_split = pl.n_split;
-    p.z = d.grid == MES_GRID_SYM ? (float)(1 << (d.bits - 1)) - 0.5f : (float)(1 << (d.bits - 1));
-    tp.x = reinterpret_cast<const uint16_t*>(x);
-    tp.k = d.k;
-    tp.d_in = d.d_in;
-    tp.n_kb_main = 4 * pl.n_chunks;
-    tp.n_tq = pl.n_tq;
-    tp.n_blk = (size_t)4 * (pl.n_chunks + pl.n_ssteps) * pl.n_tq;
-    tp.xt = reinterpret_cast<u32x4*>(ws);
-    k_prefill_tile_x<<<(unsigned)((tp.n_blk + 3) / 4), 256, 0, s>>>(tp);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    const dim3 grid(pl.n_rg, pl.n_tb, pl.n_split);
-    if (ev_start && *first_kernel && (e = hipEventRecord(ev_start, s)) != hipSuccess) return e;
-    *first_kernel = false;
-    switch (d.bits) {
-      case 1: e = launch_fused<1>(p, pl, grid, s); break;
-      case 2: e = launch_fused<2>(p, pl, grid, s); break;
-      case 3: e = launch_fused<3>(p, pl, grid, s); break;
-      default: e = launch_fused<4>(p, pl, grid, s); break;
-    }
-    if (e != hipSuccess) return e;
-    if (pl.n_split > 1) {
-      k_prefill_reduce<8, 4><<<dim3(grid.x, grid.y, 32), 256, 0, s>>>(p);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-    if (ev_stop && (e = hipEventRecord(ev_stop, s)) != hipSuccess) return e;
   }
   return hipSuccess;
 }
