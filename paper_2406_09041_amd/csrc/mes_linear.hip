@@ -445,7 +445,7 @@ struct Stream {
 
   // Salient fp16 columns ride along with the stream: the (visit, 32-column block) pairs of this workgroup
   // (pairs sp, sp + nsplit, ... of n_vis * n_sb) are dealt kSalPerChunk to a chunk, requested one chunk before
-  // they are multiplied.  A = the expert's fp16 tile as stored, B = the visit's scaled fp16 activations.
+  // they are multiplied.  A = the expert's fp16 tile (turned into D + z step, as two bf16 numbers), B = the visit's gathered activations, bf16.
   static constexpr int kSalPerChunk = 1;
   const float* step_w;   // LDS: this wavefront's steps, [slot][16 rows]
   float z;
