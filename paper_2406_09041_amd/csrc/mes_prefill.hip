@@ -114,7 +114,7 @@ struct StepData {
 };
 
 // Grid: (row groups of 16 RT output channels, token blocks of 64 NM tokens, n_split); NM + RT wavefronts in two
-// roles, spread evenly over the SIMDs.  The token blocks of up to 8 long segments (each with its own expert's codes,
+// roles, spread evenly over the SIMDs (RT = 8, or 7 where that fills the last round of workgroups: prefill_plan).  The token blocks of up to 8 long segments (each with its own expert's codes,
 // steps and salient values) share one launch, so that the compute units go from one expert's work to the next
 // without a launch in between:
 //   builders (the last RT wavefronts): builder r forms the operand of row tile r (16 output channels) for the next
@@ -276,10 +276,10 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
       for (int rt = 0; rt < RT; ++rt) {
         constexpr int kNone = -1;
         const int rn = rt < RT - 1 ? rt + 1 : 0, kn = rt < RT - 1 ? kb : (kb < 3 ? kb + 1 : kNone);
-        if (kn != kNone) a[(rt + 1) & 1] = afrag[cur][rn][kn][lane];
+        if (kn != kNone) a[(kb * RT + rt + 1) & 1] = afrag[cur][rn][kn][lane];
         __builtin_amdgcn_sched_barrier(0);               // keep the read above ahead of the matrix instructions below
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[rt & 1], xb[tt], acc[rt][tt]);
+        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[(kb * RT + rt) & 1], xb[tt], acc[rt][tt]);
       }
     }
     step_barrier();
@@ -350,7 +350,19 @@ PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tb) {
   pl.nm = 4;
   pl.n_tb = n_tb;
   pl.n_tq = pl.n_tb * 4 * pl.nm;
-  pl.n_rg = (ceil_to(d_out, kRowPad) / 16 + pl.rt - 1) / pl.rt;
+  const int n_jt = ceil_to(d_out, kRowPad) / 16;
+  pl.n_rg = (n_jt + pl.rt - 1) / pl.rt;
+  // One workgroup per compute unit at a time: the launch takes ceil(workgroups / 256) rounds of one workgroup's
+  // time, which grows with its row tiles.  7 row tiles per workgroup win where they fill the last round
+  // (14336 rows x 6 token blocks: 768 workgroups = 3 full rounds of 7 tiles against 2.6 -> 3 rounds of 8).
+  {
+    const long wg8 = (long)pl.n_rg * n_tb, rg7 = (n_jt + 6) / 7, wg7 = rg7 * n_tb;
+    const long rounds8 = (wg8 + kMaxWorkgroups - 1) / kMaxWorkgroups, rounds7 = (wg7 + kMaxWorkgroups - 1) / kMaxWorkgroups;
+    if (wg8 >= kMaxWorkgroups && rounds7 * (7 + 1) < rounds8 * (8 + 1)) {   // + 1: the part of a workgroup's time that does not shrink
+      pl.rt = 7;
+      pl.n_rg = (int)rg7;
+    }
+  }
   pl.n_chunks = ceil_to(d_in, kColPad) / 128;
   pl.n_ssteps = (ceil_to(k, kSalPad) / 32 + 3) / 4;
   const int n_steps = pl.n_chunks + pl.n_ssteps;
@@ -368,7 +380,8 @@ PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tb) {
 
 template <int BITS>
 hipError_t launch_fused(const PrefillParams& p, const PrefillPlan& pl, dim3 grid, hipStream_t s) {
-  k_prefill_fused<BITS, 8, 4><<<grid, 768, 0, s>>>(p);
+  if (pl.rt == 7) k_prefill_fused<BITS, 7, 4><<<grid, 64 * (4 + 7), 0, s>>>(p);
+  else k_prefill_fused<BITS, 8, 4><<<grid, 768, 0, s>>>(p);
   return hipGetLastError();
 }
 

@@ -561,6 +561,8 @@ def test_layer_spanning_pool_with_prefetch_gives_the_resident_result():
     (2048, 520, [0, 513], 64, 4, 0),                       # 513 tokens (a ragged third token block), 4 bits
     (264, 72, [0, 200, 205, 405, 605, 805, 1005, 1205, 1405, 1605, 1805, 1810, 2010, 2300], 5, 2, 0),
                                                            # 11 long segments: two launches of the fused kernel (8 + 3)
+    (264, 5504, [0, 512, 1000, 1536], 16, 2, 0),           # 344 row tiles x 7 token blocks: the plan takes 7 row tiles
+                                                           # per workgroup, and the last group has one tile of its own
 ])
 def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
     """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T by the fused one-product kernel (the
