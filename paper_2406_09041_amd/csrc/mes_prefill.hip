@@ -114,17 +114,21 @@ struct StepData {
 };
 
 // Grid: (row groups of 16 RT output channels, token blocks of 64 NM tokens, n_split); NM + RT wavefronts in two
-// roles, spread evenly over the SIMDs (RT = 8, or 7 where that fills the last round of workgroups: prefill_plan).  The token blocks of up to 8 long segments (each with its own expert's codes,
-// steps and salient values) share one launch, so that the compute units go from one expert's work to the next
-// without a launch in between:
+// roles, spread evenly over the SIMDs (RT = 8, or 7 where that fills the last round of workgroups: prefill_plan).
+// The token blocks of up to 8 long segments (each with its own expert's codes, steps and salient values) share one
+// launch, so that the compute units go from one expert's work to the next without a launch in between:
 //   builders (the last RT wavefronts): builder r forms the operand of row tile r (16 output channels) for the next
 //     step of 128 input channels in the idle LDS buffer, from base weight and codes requested two steps ahead;
 //   multipliers (wavefronts 0 .. NM - 1): every one multiplies all RT row tiles of the current step (from LDS) with
-//     its own 64 tokens; the activations reach it through an LDS ring of its own, filled by asynchronous copies two
-//     k blocks ahead.
+//     its own 64 tokens.  With RT = 8 the activations reach it through an LDS ring of its own, filled by
+//     asynchronous copies two k blocks ahead; with RT = 7 the 16 registers that leaves free hold a second set of
+//     activation fragments, loaded straight from memory one k block ahead (5 % faster: less LDS traffic).
 // Every workgroup reads all the activations of its tokens from L2 once per step, so the rows per workgroup set the
-// L2 traffic (without those reads the kernel was measured a third faster): RT = 8 (128 rows x 256 tokens) halves it
-// against 64 rows x 512 tokens, at the price of building every operand once per 256 tokens; it is the shape used.
+// L2 traffic: 128 rows x 256 tokens halve it against 64 rows x 512 tokens, at the price of building every operand
+// once per 256 tokens.  Measured with parts of the kernel taken out (3 experts x 512 tokens, 14336 rows; the whole
+// kernel 213 us): barriers and LDS traffic alone 88 us, + activation copies 120 us, + the builders' loads and
+// arithmetic 165 us, the matrix instructions the rest -- the parts add up rather than overlap, and what they share
+// is the LDS pipe (operands for 4 multipliers, the builders' stores, the ring's copies and reads).
 // One barrier per step.  The steps are the n_chunks chunks of input channels followed by n_ssteps steps over the
 // salient ranks; with n_split > 1 a workgroup covers a share of them and leaves its accumulators to
 // k_prefill_reduce.
@@ -133,7 +137,8 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
   constexpr int TT = 4;                                  // token tiles per multiplier
   constexpr int XD = 3;                                  // ring depth in k blocks
   __shared__ __attribute__((aligned(16))) u32x4 afrag[2][RT][4][64];     // [buffer][row tile][k block][lane]
-  __shared__ __attribute__((aligned(16))) u32x4 xring[NM][XD][TT][64];   // [multiplier][slot][token tile][lane]
+  constexpr bool kXDirect = RT <= 7;                     // activations straight into registers (RT = 8 has none to spare)
+  __shared__ __attribute__((aligned(16))) u32x4 xring[kXDirect ? 1 : NM][XD][TT][64];   // [multiplier][slot][token tile][lane]
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
@@ -235,56 +240,90 @@ __global__ __launch_bounds__(64 * (NM + RT), 1) void k_prefill_fused(const Prefi
 
   // ---- multiplier: token tiles TT (NM by + wave) .. + TT - 1 of the segment
   const int tq0 = TT * (NM * blockIdx.y + wave);
-  const char* xbase = reinterpret_cast<const char*>(p.xt + (size_t)tq0 * 64);
-  const size_t x_stride = (size_t)p.n_tq * 1024;        // bytes between k blocks
-  const int kbg_last = 4 * st1 - 1;
-  auto request_x = [&](int kbg, int slot) {             // TT copies of 1 KiB: lane l moves 16 bytes
-    const char* src = xbase + (size_t)(kbg < kbg_last ? kbg : kbg_last) * x_stride;
-#pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-      const uint32_t l = (uint32_t)(uintptr_t)&xring[wave][slot][tt][0];
-      asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                   : : "v"((uint32_t)lane * 16u), "s"(src + tt * 1024), "s"(l) : "memory", "m0");
-    }
-  };
   f32x4 acc[RT][TT];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = f32x4{0, 0, 0, 0};
-  // the copies are this wavefront's only memory loads, TT per k block, completed in order: "at most TT (XD - 1)
-  // outstanding" means the oldest requested block has arrived
-  constexpr int kXAhead = XD - 1;
+  if constexpr (kXDirect) {
+    // two register sets filled by ordinary loads one k block ahead: no LDS traffic for the activations
+    const u32x4* xsrc = p.xt + (size_t)tq0 * 64 + lane;
+    const size_t x_stride = (size_t)p.n_tq * 64;        // 16-byte units between k blocks
+    const int kbg_last = 4 * st1 - 1;
+    u32x4 xb[2][TT];
+    auto request_x = [&](int kbg, int set) {
+      const u32x4* src = xsrc + (size_t)(kbg < kbg_last ? kbg : kbg_last) * x_stride;
 #pragma unroll
-  for (int b = 0; b < kXAhead; ++b) request_x(4 * st0 + b, b);
-  int slot = 0;                                          // ring slot of the block multiplied next
-  __syncthreads();
-  for (int st = st0; st < st1; ++st) {
-    const int cur = st & 1;
-    u32x4 a[2];                                          // operands are read from LDS one row tile ahead of their use
-    a[0] = afrag[cur][0][0][lane];
+      for (int tt = 0; tt < TT; ++tt) xb[set][tt] = src[tt * 64];
+    };
+    request_x(4 * st0, 0);
+    __syncthreads();
+    for (int st = st0; st < st1; ++st) {
+      const int cur = st & 1;
+      u32x4 a[2];                                        // operands are read from LDS one row tile ahead of their use
+      a[0] = afrag[cur][0][0][lane];
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-      const int ahead = slot + kXAhead < XD ? slot + kXAhead : slot + kXAhead - XD;   // the slot multiplied last
-      request_x(4 * st + kb + kXAhead, ahead);
-      asm volatile("s_waitcnt vmcnt(%0)" : : "n"(TT * kXAhead) : "memory");
-      u32x4 xb[TT];
+      for (int kb = 0; kb < 4; ++kb) {
+        request_x(4 * st + kb + 1, (kb + 1) & 1);
 #pragma unroll
-      for (int tt = 0; tt < TT; ++tt) xb[tt] = xring[wave][slot][tt][lane];
-      slot = slot + 1 < XD ? slot + 1 : 0;
+        for (int rt = 0; rt < RT; ++rt) {
+          constexpr int kNone = -1;
+          const int rn = rt < RT - 1 ? rt + 1 : 0, kn = rt < RT - 1 ? kb : (kb < 3 ? kb + 1 : kNone);
+          if (kn != kNone) a[(kb * RT + rt + 1) & 1] = afrag[cur][rn][kn][lane];
+          __builtin_amdgcn_sched_barrier(0);             // keep the read above ahead of the matrix instructions below
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        constexpr int kNone = -1;
-        const int rn = rt < RT - 1 ? rt + 1 : 0, kn = rt < RT - 1 ? kb : (kb < 3 ? kb + 1 : kNone);
-        if (kn != kNone) a[(kb * RT + rt + 1) & 1] = afrag[cur][rn][kn][lane];
-        __builtin_amdgcn_sched_barrier(0);               // keep the read above ahead of the matrix instructions below
-#pragma unroll
-        for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[(kb * RT + rt) & 1], xb[tt], acc[rt][tt]);
+          for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[(kb * RT + rt) & 1], xb[kb & 1][tt], acc[rt][tt]);
+        }
       }
+      step_barrier();
     }
-    step_barrier();
+  } else {
+    const char* xbase = reinterpret_cast<const char*>(p.xt + (size_t)tq0 * 64);
+    const size_t x_stride = (size_t)p.n_tq * 1024;        // bytes between k blocks
+    const int kbg_last = 4 * st1 - 1;
+    auto request_x = [&](int kbg, int slot) {             // TT copies of 1 KiB: lane l moves 16 bytes
+      const char* src = xbase + (size_t)(kbg < kbg_last ? kbg : kbg_last) * x_stride;
+#pragma unroll
+      for (int tt = 0; tt < TT; ++tt) {
+        const uint32_t l = (uint32_t)(uintptr_t)&xring[wave][slot][tt][0];
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     : : "v"((uint32_t)lane * 16u), "s"(src + tt * 1024), "s"(l) : "memory", "m0");
+      }
+    };
+    // the copies are this wavefront's only memory loads, TT per k block, completed in order: "at most TT (XD - 1)
+    // outstanding" means the oldest requested block has arrived
+    constexpr int kXAhead = XD - 1;
+#pragma unroll
+    for (int b = 0; b < kXAhead; ++b) request_x(4 * st0 + b, b);
+    int slot = 0;                                          // ring slot of the block multiplied next
+    __syncthreads();
+    for (int st = st0; st < st1; ++st) {
+      const int cur = st & 1;
+      u32x4 a[2];                                          // operands are read from LDS one row tile ahead of their use
+      a[0] = afrag[cur][0][0][lane];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb) {
+        const int ahead = slot + kXAhead < XD ? slot + kXAhead : slot + kXAhead - XD;   // the slot multiplied last
+        request_x(4 * st + kb + kXAhead, ahead);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(TT * kXAhead) : "memory");
+        u32x4 xb[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) xb[tt] = xring[wave][slot][tt][lane];
+        slot = slot + 1 < XD ? slot + 1 : 0;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+          constexpr int kNone = -1;
+          const int rn = rt < RT - 1 ? rt + 1 : 0, kn = rt < RT - 1 ? kb : (kb < 3 ? kb + 1 : kNone);
+          if (kn != kNone) a[(kb * RT + rt + 1) & 1] = afrag[cur][rn][kn][lane];
+          __builtin_amdgcn_sched_barrier(0);               // keep the read above ahead of the matrix instructions below
+#pragma unroll
+          for (int tt = 0; tt < TT; ++tt) acc[rt][tt] = mfma_bf16(a[(kb * RT + rt) & 1], xb[tt], acc[rt][tt]);
+        }
+      }
+      step_barrier();
+    }
+    asm volatile("s_waitcnt vmcnt(0)" : : : "memory");     // the surplus copies must land before the LDS is given back
   }
-  asm volatile("s_waitcnt vmcnt(0)" : : : "memory");     // the surplus copies must land before the LDS is given back
 
   if (p.n_split > 1) {   // this workgroup saw a share of the contraction only: leave the tiles, in thread order
     constexpr int NT = 64 * NM;
@@ -354,11 +393,13 @@ PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tb) {
   pl.n_rg = (n_jt + pl.rt - 1) / pl.rt;
   // One workgroup per compute unit at a time: the launch takes ceil(workgroups / 256) rounds of one workgroup's
   // time, which grows with its row tiles.  7 row tiles per workgroup win where they fill the last round
-  // (14336 rows x 6 token blocks: 768 workgroups = 3 full rounds of 7 tiles against 2.6 -> 3 rounds of 8).
+  // (14336 rows x 6 token blocks: 768 workgroups = 3 full rounds of 7 tiles against 2.6 -> 3 rounds of 8); + 1 below:
+  // the part of a workgroup's time that does not shrink with its rows.  (Equal tile-rounds -- 14336 rows x 16 token
+  // blocks: 8 rounds of 7 or 7 rounds of 8 -- measured no better with 7.)
   {
     const long wg8 = (long)pl.n_rg * n_tb, rg7 = (n_jt + 6) / 7, wg7 = rg7 * n_tb;
     const long rounds8 = (wg8 + kMaxWorkgroups - 1) / kMaxWorkgroups, rounds7 = (wg7 + kMaxWorkgroups - 1) / kMaxWorkgroups;
-    if (wg8 >= kMaxWorkgroups && rounds7 * (7 + 1) < rounds8 * (8 + 1)) {   // + 1: the part of a workgroup's time that does not shrink
+    if (wg8 >= kMaxWorkgroups && rounds7 * (7 + 1) < rounds8 * (8 + 1)) {
       pl.rt = 7;
       pl.n_rg = (int)rg7;
     }
