@@ -563,6 +563,9 @@ def test_layer_spanning_pool_with_prefetch_gives_the_resident_result():
                                                            # 11 long segments: two launches of the fused kernel (8 + 3)
     (264, 5504, [0, 512, 1000, 1536], 16, 2, 0),           # 344 row tiles x 7 token blocks: the plan takes 7 row tiles
                                                            # per workgroup, and the last group has one tile of its own
+    (264, 5504, [0, 512, 1000, 1536], 16, 1, 0),           # the same plan at 1, 3 and 4 bits
+    (264, 5504, [0, 512, 1000, 1536], 40, 3, 1),
+    (264, 5504, [0, 512, 1000, 1536], 0, 4, 0),
 ])
 def test_long_segments_take_the_one_product_path(d_in, d_out, seg, k, bits, grid):
     """Expert segments of 192 tokens or more are computed as x (W + Delta~)^T by the fused one-product kernel (the
