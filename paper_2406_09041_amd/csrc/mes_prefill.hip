@@ -392,14 +392,15 @@ PrefillPlan prefill_plan(int d_in, int d_out, int k, int n_tb) {
   const int n_jt = ceil_to(d_out, kRowPad) / 16;
   pl.n_rg = (n_jt + pl.rt - 1) / pl.rt;
   // One workgroup per compute unit at a time: the launch takes ceil(workgroups / 256) rounds of one workgroup's
-  // time, which grows with its row tiles.  7 row tiles per workgroup win where they fill the last round
-  // (14336 rows x 6 token blocks: 768 workgroups = 3 full rounds of 7 tiles against 2.6 -> 3 rounds of 8); + 1 below:
-  // the part of a workgroup's time that does not shrink with its rows.  (Equal tile-rounds -- 14336 rows x 16 token
-  // blocks: 8 rounds of 7 or 7 rounds of 8 -- measured no better with 7.)
+  // time, which grows with its row tiles.  7 row tiles per workgroup win where they fill the last round better
+  // (14336 rows x 6 token blocks: 768 workgroups = 3 full rounds of 7 tiles against 2.6 -> 3 rounds of 8; 4096 rows x
+  // 6 blocks: one round of 222 workgroups against one of 192); + 1 below: the part of a workgroup's time that does
+  // not shrink with its rows.  (Equal tile-rounds -- 14336 rows x 16 token blocks: 8 rounds of 7 or 7 rounds of 8 --
+  // measured no better with 7.)  128 workgroups or fewer split the contraction instead and keep 8 tiles.
   {
     const long wg8 = (long)pl.n_rg * n_tb, rg7 = (n_jt + 6) / 7, wg7 = rg7 * n_tb;
     const long rounds8 = (wg8 + kMaxWorkgroups - 1) / kMaxWorkgroups, rounds7 = (wg7 + kMaxWorkgroups - 1) / kMaxWorkgroups;
-    if (wg8 >= kMaxWorkgroups && rounds7 * (7 + 1) < rounds8 * (8 + 1)) {
+    if (2 * wg8 > kMaxWorkgroups && rounds7 * (7 + 1) < rounds8 * (8 + 1)) {
       pl.rt = 7;
       pl.n_rg = (int)rg7;
     }
